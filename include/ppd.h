@@ -1,0 +1,177 @@
+/* libppd: Predictive Pipelined Decoding (PPD) on one MI355X (gfx950).
+ *
+ * The calls follow the paper's statement of the method (Sec. 3, Algorithm 1;
+ * general exit layer: Appendix C, Algorithm 2).  Inputs of the method: number
+ * of tokens l, number of decoder layers d, exit layer dbar >= d/2, number of
+ * early candidates k, start token x_0.  Output: the token sequence of plain
+ * greedy decoding, exactly.
+ *
+ * Where the paper runs k sub-processes on k extra compute units, this
+ * library runs the k candidate tokens as k extra rows of the same kernel
+ * launches on one GPU: during the parallel phase of a round, step j handles
+ * the main token at layer dbar+j and the k candidates at layer j.
+ *
+ * Pointer kinds are stated per argument: HOST or DEVICE.  All functions
+ * return 0 on success or a negative PPD_E* code; a failing call leaves the
+ * context unchanged unless stated.  One context must be used by one thread
+ * at a time.  No C++ exception crosses this boundary.
+ */
+#ifndef PPD_H
+#define PPD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PPD_OK 0
+#define PPD_EINVAL (-1) /* bad dims, k outside [1, PPD_MAX_K], exit layer outside [ceil(d/2), d-1], null pointer */
+#define PPD_ENOMEM (-2) /* device or host allocation failed */
+#define PPD_ECTX (-3)   /* context window exhausted */
+#define PPD_ESTATE (-4) /* call out of order (e.g. step before prefill) */
+#define PPD_EHIP (-5)   /* a HIP call failed; ppd_last_hip_error() tells which */
+
+#define PPD_MAX_K 8
+
+typedef struct ppd_ctx ppd_ctx; /* opaque */
+
+/* Shape of the decoder-only transformer the rounds run on.  The paper treats
+ * the transformer layer as a black box of equal cost per layer (Fig. 1,
+ * Sec. 4.1); these fields select the block the benchmark configurations name. */
+typedef struct {
+  int32_t n_layers;  /* d */
+  int32_t d_model;   /* multiple of 8 */
+  int32_t n_heads;
+  int32_t head_dim;  /* 64 or 128; n_heads * head_dim == d_model */
+  int32_t d_ff;      /* multiple of 8 */
+  int32_t vocab;
+  int32_t max_ctx;   /* positions the KV cache (and the position table) holds */
+  int32_t norm;      /* 0 LayerNorm with bias, 1 RMSNorm */
+  int32_t act;       /* 0 GELU (erf form), 1 ReLU, 2 SwiGLU */
+  int32_t pos;       /* 0 learned absolute position table, 1 RoPE (rotate-half pairs i, i+head_dim/2) */
+  int32_t has_bias;  /* linear layers carry biases */
+  int32_t wdtype;    /* 0 fp32, 1 bf16: type of every weight tensor and of the KV cache */
+  float norm_eps;
+  float rope_theta;
+  int32_t eos_id;    /* -1: never stop */
+} ppd_model_dims;
+
+/* DEVICE pointers to the weights, borrowed for the life of the context (the
+ * caller keeps them alive and unchanged).  Linear weights are row-major
+ * [out][in]; all tensors have type `wdtype` and 16-byte aligned rows.
+ * The per-layer members are HOST arrays of n_layers DEVICE pointers.
+ * Members a model does not have (biases, pos_emb, w_up, LayerNorm biases)
+ * may be NULL. */
+typedef struct {
+  const void *tok_emb;  /* [vocab][d_model] */
+  const void *pos_emb;  /* [max_ctx][d_model], pos == 0 only */
+  const void *lnf_g, *lnf_b; /* final norm */
+  const void *lm_head;  /* [vocab][d_model] */
+  const void *early_head; /* [vocab][d_model] classifier for the early prediction, NULL: lm_head
+                             (Sec. 4.3: classifier of the final layer reused, or one trained per layer) */
+  const void *const *ln1_g, *const *ln1_b;
+  const void *const *wq, *const *wk, *const *wv, *const *wo; /* [d_model][d_model] */
+  const void *const *bq, *const *bk, *const *bv, *const *bo;
+  const void *const *ln2_g, *const *ln2_b;
+  const void *const *w_in;  /* [d_ff][d_model]; the gate matrix for SwiGLU */
+  const void *const *w_up;  /* [d_ff][d_model], SwiGLU only */
+  const void *const *w_out; /* [d_model][d_ff] */
+  const void *const *b_in, *const *b_out;
+} ppd_weights;
+
+/* What one round did (Algorithm 2, one iteration of the while loop). */
+typedef struct {
+  int32_t token;     /* x_{t+1}: arg max of the final layer's logits, ties to the lowest id */
+  int32_t matched;   /* 1 if one early candidate equals token: the next round resumes mid-stack */
+  int32_t match_idx; /* index of that candidate in cand[], or -1 */
+  int32_t cand[PPD_MAX_K]; /* early top-k ids, by (logit descending, id ascending); entries >= k are -1 */
+} ppd_step_info;
+
+/* Counters in the units of Sec. 4: one layer on one token = one unit. */
+typedef struct {
+  uint64_t rounds;            /* tokens emitted by ppd_step */
+  uint64_t matches;           /* rounds with matched == 1 */
+  uint64_t runs;              /* N of Sec. 4.1: rounds that started from layer 1 */
+  uint64_t main_layer_rows;   /* layer executions of the main token: latency in time units */
+  uint64_t branch_layer_rows; /* layer executions of candidate rows */
+  uint64_t plain_steps;       /* tokens emitted by plain_greedy_step */
+  uint64_t weight_bytes;      /* weight bytes the launched kernels had to stream */
+  uint64_t kv_bytes;          /* KV-cache bytes the launched attention kernels had to read */
+} ppd_stats;
+
+/* Kernel classes for ppd_get_kernel_time(). */
+enum {
+  PPD_KC_EMBED = 0,
+  PPD_KC_GEMM_QKV,   /* norm + Q,K,V projections */
+  PPD_KC_ATTN,       /* RoPE, KV write, attention over prefix + own position */
+  PPD_KC_ATTN_MERGE, /* merge of the position-chunk partials */
+  PPD_KC_GEMM_O,     /* output projection + residual */
+  PPD_KC_GEMM_FFN_IN,  /* norm + first FFN matrix (both matrices for SwiGLU) + activation */
+  PPD_KC_GEMM_FFN_OUT, /* second FFN matrix + residual */
+  PPD_KC_HEAD,       /* final norm + LM head */
+  PPD_KC_SELECT,     /* top-k / arg max / verification */
+  PPD_KC_COMMIT,     /* adoption of the matching candidate: hidden row + KV tail -> cache */
+  PPD_KC_COUNT
+};
+
+/* Create a context.  Sec. 3 / Algorithm 2 inputs: d (dims->n_layers), dbar
+ * (exit_layer, 1-based: the early prediction reads the output of that layer,
+ * ceil(d/2) <= exit_layer <= d-1 as Theorem 4.1 requires dbar >= d/2), k.
+ * dims, w: HOST structs, copied.  hip_stream: a hipStream_t (NULL = the
+ * default stream); all work of this context is issued on it.  The KV cache,
+ * the candidates' KV tails and all scratch are allocated here (device
+ * memory, freed by ppd_destroy).  *out receives the context (HOST). */
+int ppd_create(const ppd_model_dims *dims, const ppd_weights *w, int k, int exit_layer,
+               void *hip_stream, ppd_ctx **out);
+
+/* Forget the sequence: KV cache length 0, round state cleared, counters zeroed. */
+int ppd_reset(ppd_ctx *ctx);
+
+/* Feed a prompt (HOST int32 ids, n_prompt >= 1).  The algorithm starts from
+ * one start token x_0; reading taken for prompts: positions 0..n_prompt-2 are
+ * run through all d layers to fill the KV cache, the last prompt token
+ * becomes x_0 with match = False.  Implies ppd_reset.  PPD_ECTX if
+ * n_prompt > max_ctx; PPD_EINVAL for ids outside [0, vocab). */
+int ppd_prefill(ppd_ctx *ctx, const int32_t *prompt, int n_prompt);
+
+/* One round of Algorithm 2: main token to the exit layer (from layer 1, or
+ * from layer d-dbar+1 after a match), early top-k, the parallel phase of
+ * d-dbar pipelined steps, final arg max, verification, adoption or discard.
+ * Writes the emitted token to out_tokens[0] (HOST, max_out >= 1) and returns
+ * the number of tokens written: 1, or 0 once the previous token was EOS.
+ * info (HOST, nullable) receives the round's record.  PPD_ECTX when position
+ * t+1 would not fit in max_ctx.  Synchronous: the stream is idle on return. */
+int ppd_step(ppd_ctx *ctx, int32_t *out_tokens, int max_out, ppd_step_info *info);
+
+/* Conventional decoding of one token (Sec. 4.2: d time units per token): all
+ * d layers on the pending token, final arg max.  Same kernels, one row.
+ * Writes the token to *out_token (HOST); returns 1, or 0 after EOS.  May be
+ * mixed with ppd_step on one context: a pending match is dropped. */
+int plain_greedy_step(ppd_ctx *ctx, int32_t *out_token);
+
+/* Test hooks.  host_logits: HOST float[vocab].  Final-layer logits of the last
+ * ppd_step / plain_greedy_step, and early-exit logits of the last ppd_step. */
+int ppd_get_logits(ppd_ctx *ctx, float *host_logits);
+int ppd_get_early_logits(ppd_ctx *ctx, float *host_logits);
+
+/* Copy the counters (HOST). */
+int ppd_get_stats(const ppd_ctx *ctx, ppd_stats *out);
+
+/* Per-kernel timing with HIP events on the context's stream.  While enabled
+ * every launch is bracketed by two events; ppd_get_kernel_time returns, for
+ * one kernel class, the summed elapsed milliseconds and the number of
+ * launches since profiling was enabled (HOST outputs). */
+int ppd_set_profiling(ppd_ctx *ctx, int on);
+int ppd_get_kernel_time(ppd_ctx *ctx, int kernel_class, double *ms_total, uint64_t *launches);
+
+void ppd_destroy(ppd_ctx *ctx);
+
+const char *ppd_strerror(int code);
+/* hipError_t value of the last failing HIP call on this context (0 if none). */
+int ppd_last_hip_error(const ppd_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PPD_H */

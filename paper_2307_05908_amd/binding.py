@@ -1,0 +1,205 @@
+"""ctypes binding of libppd (include/ppd.h): argument marshalling only.
+
+Every step of the decode path runs in the HIP kernels behind the C ABI; this
+module turns torch device tensors into the pointer tables the library takes
+and mirrors its entry points under the same names.  There is no CPU fallback:
+if the library cannot be loaded, importing the symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional
+
+import numpy as np
+
+from . import build as _build
+
+PPD_MAX_K = 8
+KERNEL_CLASSES = ("embed", "gemm_qkv", "attn", "attn_merge", "gemm_o", "gemm_ffn_in", "gemm_ffn_out",
+                  "head", "select", "commit")
+_LAYER_FIELDS = ("ln1_g", "ln1_b", "wq", "wk", "wv", "wo", "bq", "bk", "bv", "bo",
+                 "ln2_g", "ln2_b", "w_in", "w_up", "w_out", "b_in", "b_out")
+# order of the per-layer members in ppd_weights
+_W_LAYER_ORDER = ("ln1_g", "ln1_b", "wq", "wk", "wv", "wo", "bq", "bk", "bv", "bo",
+                  "ln2_g", "ln2_b", "w_in", "w_up", "w_out", "b_in", "b_out")
+
+
+class ModelDims(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_layers", "d_model", "n_heads", "head_dim", "d_ff", "vocab", "max_ctx",
+                 "norm", "act", "pos", "has_bias", "wdtype")] + \
+               [("norm_eps", ctypes.c_float), ("rope_theta", ctypes.c_float), ("eos_id", ctypes.c_int32)]
+
+
+class Weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("tok_emb", "pos_emb", "lnf_g", "lnf_b", "lm_head", "early_head")] + \
+               [(n, ctypes.POINTER(ctypes.c_void_p)) for n in _W_LAYER_ORDER]
+
+
+class StepInfo(ctypes.Structure):
+    _fields_ = [("token", ctypes.c_int32), ("matched", ctypes.c_int32), ("match_idx", ctypes.c_int32),
+                ("cand", ctypes.c_int32 * PPD_MAX_K)]
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in
+                ("rounds", "matches", "runs", "main_layer_rows", "branch_layer_rows", "plain_steps",
+                 "weight_bytes", "kv_bytes")]
+
+
+EXPORTS = ("ppd_create", "ppd_reset", "ppd_prefill", "ppd_step", "plain_greedy_step", "ppd_get_logits",
+           "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_get_kernel_time", "ppd_destroy",
+           "ppd_strerror", "ppd_last_hip_error")
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libppd.so (built in-tree).  Raises if it is missing and cannot be built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build(True)
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.ppd_create.argtypes = [ctypes.POINTER(ModelDims), ctypes.POINTER(Weights), ci, ci, vp, ctypes.POINTER(vp)]
+    lib.ppd_reset.argtypes = [vp]
+    lib.ppd_prefill.argtypes = [vp, vp, ci]
+    lib.ppd_step.argtypes = [vp, vp, ci, ctypes.POINTER(StepInfo)]
+    lib.plain_greedy_step.argtypes = [vp, vp]
+    lib.ppd_get_logits.argtypes = [vp, vp]
+    lib.ppd_get_early_logits.argtypes = [vp, vp]
+    lib.ppd_get_stats.argtypes = [vp, ctypes.POINTER(Stats)]
+    lib.ppd_set_profiling.argtypes = [vp, ci]
+    lib.ppd_get_kernel_time.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
+    lib.ppd_destroy.argtypes = [vp]
+    lib.ppd_destroy.restype = None
+    lib.ppd_strerror.argtypes = [ci]
+    lib.ppd_strerror.restype = ctypes.c_char_p
+    lib.ppd_last_hip_error.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+class PPDError(RuntimeError):
+    def __init__(self, code: int, what: str, hip: int = 0):
+        msg = load_library().ppd_strerror(code).decode()
+        super().__init__(f"{what}: {msg} (code {code}" + (f", hipError {hip})" if hip else ")"))
+        self.code = code
+
+
+def upload_model(model, device="cuda:0") -> Dict[str, object]:
+    """Copy a host model (``cfg``, ``g``, ``layers`` of numpy arrays; bf16 as uint16 bits) to the GPU.
+    Returns {name: tensor or list of tensors}; torch is used for device memory only."""
+    import torch
+
+    def up(a):
+        if a is None:
+            return None
+        t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a)
+        t = t.to(device)
+        return t.view(torch.bfloat16) if a.dtype == np.uint16 else t
+
+    dev = {k: up(v) for k, v in model.g.items()}
+    for f in _LAYER_FIELDS:
+        dev[f] = [up(a) for a in model.layers[f]]
+    return dev
+
+
+class PPD:
+    """One decoding context.  ``dev`` is what ``upload_model`` returned (kept alive here)."""
+
+    def __init__(self, cfg, dev: Dict[str, object], k: Optional[int] = None, exit_layer: Optional[int] = None,
+                 eos_id: int = -1, early_head=None, stream=None):
+        import torch
+        lib = load_library()
+        self.cfg, self.dev = cfg, dev
+        self.k = cfg.k if k is None else k
+        self.exit_layer = cfg.exit_layer if exit_layer is None else exit_layer
+        d = ModelDims(cfg.n_layers, cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.d_ff, cfg.vocab, cfg.max_ctx,
+                      cfg.norm, cfg.act, cfg.pos, cfg.has_bias, cfg.wdtype, cfg.norm_eps, cfg.rope_theta, eos_id)
+        w = Weights()
+
+        def ptr(t):
+            return None if t is None else t.data_ptr()
+
+        for n in ("tok_emb", "pos_emb", "lnf_g", "lnf_b", "lm_head"):
+            setattr(w, n, ptr(dev.get(n)))
+        self._early = early_head
+        w.early_head = ptr(early_head)
+        self._tabs = []
+        for f in _W_LAYER_ORDER:
+            tab = (ctypes.c_void_p * cfg.n_layers)(*[ptr(t) for t in dev[f]])
+            self._tabs.append(tab)
+            setattr(w, f, tab)
+        self._stream = stream if stream is not None else torch.cuda.current_stream()
+        h = ctypes.c_void_p()
+        rc = lib.ppd_create(ctypes.byref(d), ctypes.byref(w), self.k, self.exit_layer,
+                            ctypes.c_void_p(self._stream.cuda_stream), ctypes.byref(h))
+        if rc != 0:
+            raise PPDError(rc, "ppd_create")
+        self._h = h
+        self._tok = np.zeros(4, dtype=np.int32)
+        self._logits = np.zeros(cfg.vocab, dtype=np.float32)
+
+    def _chk(self, rc: int, what: str) -> int:
+        if rc < 0:
+            raise PPDError(rc, what, load_library().ppd_last_hip_error(self._h))
+        return rc
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().ppd_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def ppd_reset(self):
+        self._chk(load_library().ppd_reset(self._h), "ppd_reset")
+
+    def ppd_prefill(self, prompt):
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        self._chk(load_library().ppd_prefill(self._h, p.ctypes.data, len(p)), "ppd_prefill")
+
+    def ppd_step(self, want_info: bool = True):
+        """One round.  Returns (token or None after EOS, StepInfo or None)."""
+        info = StepInfo() if want_info else None
+        n = self._chk(load_library().ppd_step(self._h, self._tok.ctypes.data, 1,
+                                              ctypes.byref(info) if want_info else None), "ppd_step")
+        return (int(self._tok[0]) if n == 1 else None), info
+
+    def plain_greedy_step(self):
+        n = self._chk(load_library().plain_greedy_step(self._h, self._tok.ctypes.data), "plain_greedy_step")
+        return int(self._tok[0]) if n == 1 else None
+
+    def ppd_get_logits(self) -> np.ndarray:
+        self._chk(load_library().ppd_get_logits(self._h, self._logits.ctypes.data), "ppd_get_logits")
+        return self._logits.copy()
+
+    def ppd_get_early_logits(self) -> np.ndarray:
+        self._chk(load_library().ppd_get_early_logits(self._h, self._logits.ctypes.data), "ppd_get_early_logits")
+        return self._logits.copy()
+
+    def ppd_get_stats(self) -> Dict[str, int]:
+        s = Stats()
+        self._chk(load_library().ppd_get_stats(self._h, ctypes.byref(s)), "ppd_get_stats")
+        return {n: int(getattr(s, n)) for n, _ in Stats._fields_}
+
+    def ppd_set_profiling(self, on: bool):
+        self._chk(load_library().ppd_set_profiling(self._h, int(on)), "ppd_set_profiling")
+
+    def ppd_get_kernel_time(self) -> Dict[str, Dict[str, float]]:
+        out = {}
+        ms, n = ctypes.c_double(), ctypes.c_uint64()
+        for i, name in enumerate(KERNEL_CLASSES):
+            self._chk(load_library().ppd_get_kernel_time(self._h, i, ctypes.byref(ms), ctypes.byref(n)),
+                      "ppd_get_kernel_time")
+            out[name] = {"ms": ms.value, "launches": int(n.value)}
+        return out

