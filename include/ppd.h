@@ -112,6 +112,8 @@ enum {
   PPD_KC_HEAD,       /* final norm + LM head */
   PPD_KC_SELECT,     /* top-k / arg max / verification */
   PPD_KC_COMMIT,     /* adoption of the matching candidate: hidden row + KV tail -> cache */
+  PPD_KC_PHASE,      /* not a kernel: one bracket around a whole phase of a round (groups = 1: the
+                        main token alone up to the exit layer; groups = 2: the d-dbar pipelined steps) */
   PPD_KC_COUNT
 };
 
@@ -160,15 +162,18 @@ int ppd_get_stats(const ppd_ctx *ctx, ppd_stats *out);
 
 /* Per-kernel timing with HIP events on the context's stream.  While enabled
  * every launch is bracketed by two events; ppd_get_kernel_time returns, for
- * one kernel class, the summed elapsed milliseconds and the number of
- * launches since profiling was enabled (HOST outputs). */
+ * one kernel class and one launch shape (groups = 1: one row group, the main
+ * token alone; groups = 2: a pipelined step's launch, main row + k candidate
+ * rows), the summed elapsed milliseconds and the number of launches since
+ * profiling was enabled (HOST outputs).  Prefill is never profiled. */
 int ppd_set_profiling(ppd_ctx *ctx, int on);
-int ppd_get_kernel_time(ppd_ctx *ctx, int kernel_class, double *ms_total, uint64_t *launches);
+int ppd_get_kernel_time(ppd_ctx *ctx, int kernel_class, int groups, double *ms_total, uint64_t *launches);
 
 void ppd_destroy(ppd_ctx *ctx);
 
 const char *ppd_strerror(int code);
-/* hipError_t value of the last failing HIP call on this context (0 if none). */
+/* hipError_t value of the last failing HIP call on this context (0 if none); with ctx == NULL, of the
+ * last ppd_create that failed. */
 int ppd_last_hip_error(const ppd_ctx *ctx);
 
 #ifdef __cplusplus

@@ -17,7 +17,7 @@ from . import build as _build
 
 PPD_MAX_K = 8
 KERNEL_CLASSES = ("embed", "gemm_qkv", "attn", "attn_merge", "gemm_o", "gemm_ffn_in", "gemm_ffn_out",
-                  "head", "select", "commit")
+                  "head", "select", "commit", "phase")
 _LAYER_FIELDS = ("ln1_g", "ln1_b", "wq", "wk", "wv", "wo", "bq", "bk", "bv", "bo",
                  "ln2_g", "ln2_b", "w_in", "w_up", "w_out", "b_in", "b_out")
 # order of the per-layer members in ppd_weights
@@ -63,6 +63,10 @@ def load_library() -> ctypes.CDLL:
         return _lib
     if not os.path.exists(_build.LIB_PATH):
         _build.build(True)
+    # torch ships its own HIP runtime (same soname).  Import it first so that libppd binds to the
+    # runtime that owns the caller's tensors and streams; loaded the other way round the process
+    # would hold two HIP runtimes and device pointers of one would be unknown to the other.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_build.LIB_PATH)
     vp, ci = ctypes.c_void_p, ctypes.c_int
     lib.ppd_create.argtypes = [ctypes.POINTER(ModelDims), ctypes.POINTER(Weights), ci, ci, vp, ctypes.POINTER(vp)]
@@ -74,7 +78,7 @@ def load_library() -> ctypes.CDLL:
     lib.ppd_get_early_logits.argtypes = [vp, vp]
     lib.ppd_get_stats.argtypes = [vp, ctypes.POINTER(Stats)]
     lib.ppd_set_profiling.argtypes = [vp, ci]
-    lib.ppd_get_kernel_time.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
+    lib.ppd_get_kernel_time.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
     lib.ppd_destroy.argtypes = [vp]
     lib.ppd_destroy.restype = None
     lib.ppd_strerror.argtypes = [ci]
@@ -140,7 +144,7 @@ class PPD:
         rc = lib.ppd_create(ctypes.byref(d), ctypes.byref(w), self.k, self.exit_layer,
                             ctypes.c_void_p(self._stream.cuda_stream), ctypes.byref(h))
         if rc != 0:
-            raise PPDError(rc, "ppd_create")
+            raise PPDError(rc, "ppd_create", lib.ppd_last_hip_error(None))
         self._h = h
         self._tok = np.zeros(4, dtype=np.int32)
         self._logits = np.zeros(cfg.vocab, dtype=np.float32)
@@ -198,8 +202,10 @@ class PPD:
     def ppd_get_kernel_time(self) -> Dict[str, Dict[str, float]]:
         out = {}
         ms, n = ctypes.c_double(), ctypes.c_uint64()
-        for i, name in enumerate(KERNEL_CLASSES):
-            self._chk(load_library().ppd_get_kernel_time(self._h, i, ctypes.byref(ms), ctypes.byref(n)),
-                      "ppd_get_kernel_time")
-            out[name] = {"ms": ms.value, "launches": int(n.value)}
+        for groups in (1, 2):
+            for i, name in enumerate(KERNEL_CLASSES):
+                self._chk(load_library().ppd_get_kernel_time(self._h, i, groups, ctypes.byref(ms), ctypes.byref(n)),
+                          "ppd_get_kernel_time")
+                if n.value:
+                    out[f"{name}.g{groups}"] = {"ms": ms.value, "launches": int(n.value)}
         return out

@@ -62,11 +62,13 @@ struct ppd_ctx {
   std::vector<hipEvent_t> ev;   // pairs
   std::vector<int> ev_class;
   size_t ev_used;
-  double kc_ms[PPD_KC_COUNT];
-  uint64_t kc_n[PPD_KC_COUNT];
+  double kc_ms[2 * PPD_KC_COUNT];   // [groups-1][class]
+  uint64_t kc_n[2 * PPD_KC_COUNT];
 };
 
 namespace {
+
+int g_create_hip_error = 0;   // hipError_t of the last ppd_create that failed with PPD_EHIP / PPD_ENOMEM
 
 #define HIPCHK(ctx, call)                       \
   do {                                          \
@@ -81,7 +83,7 @@ inline size_t cache_layer_bytes(const ppd_ctx* c) { return (size_t)c->d.max_ctx 
 
 struct ProfScope {
   ppd_ctx* c; int cls; size_t idx; bool on;
-  ProfScope(ppd_ctx* c_, int cls_) : c(c_), cls(cls_), idx(0), on(c_->prof != 0) {
+  ProfScope(ppd_ctx* c_, int cls_, int groups = 1) : c(c_), cls(cls_ + (groups - 1) * PPD_KC_COUNT), idx(0), on(c_->prof != 0) {
     if (!on) return;
     if (c->ev_used + 2 > c->ev.size()) {
       for (int i = 0; i < 2; ++i) { hipEvent_t e; if (hipEventCreate(&e) != hipSuccess) { on = false; return; } c->ev.push_back(e); }
@@ -200,7 +202,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
     }
     a.K = dm; a.N[0] = a.N[1] = a.N[2] = dm; a.ntot = 3 * dm; a.ldx = dm; a.ldy = 3 * dm;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
-    ProfScope ps(c, PPD_KC_GEMM_QKV);
+    ProfScope ps(c, PPD_KC_GEMM_QKV, ngroups);
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   // 2. RoPE + KV write + attention partials, then merge
@@ -231,10 +233,10 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
     a.rope = d.pos == 1 ? c->rope : nullptr;
     a.H = d.n_heads; a.d_model = dm; a.max_ctx = d.max_ctx; a.nchunk_max = c->nchunk_max;
     a.scale = 1.0f / sqrtf((float)d.head_dim);
-    { ProfScope ps(c, PPD_KC_ATTN); HIPCHK(c, launch_attn(c, a, ngroups)); }
+    { ProfScope ps(c, PPD_KC_ATTN, ngroups); HIPCHK(c, launch_attn(c, a, ngroups)); }
     mg.H = d.n_heads; mg.HD = d.head_dim; mg.d_model = dm; mg.nchunk_max = c->nchunk_max;
     int mmax = rg[0].M; if (ngroups == 2 && rg[1].M > mmax) mmax = rg[1].M;
-    ProfScope ps(c, PPD_KC_ATTN_MERGE);
+    ProfScope ps(c, PPD_KC_ATTN_MERGE, ngroups);
     hipLaunchKernelGGL(attn_merge_kernel, dim3(mmax, d.n_heads, ngroups), dim3(d.head_dim), 0, c->stream, mg);
     HIPCHK(c, hipGetLastError());
   }
@@ -248,7 +250,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
       G.W[0] = w.wo; G.B[0] = bias ? w.bo : nullptr; G.M = rg[g].M;
     }
     a.K = dm; a.N[0] = dm; a.ntot = dm; a.ldx = dm; a.ldy = dm; a.norm = -1; a.act = 0;
-    ProfScope ps(c, PPD_KC_GEMM_O);
+    ProfScope ps(c, PPD_KC_GEMM_O, ngroups);
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   // 4. norm2 + FFN in (+ gate/up pairing) + activation
@@ -265,7 +267,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
     }
     a.K = dm; a.N[0] = F; a.N[1] = swiglu ? F : 0; a.ntot = F; a.ldx = dm; a.ldy = F;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = swiglu ? 3 : (d.act == 0 ? 1 : 2);
-    ProfScope ps(c, PPD_KC_GEMM_FFN_IN);
+    ProfScope ps(c, PPD_KC_GEMM_FFN_IN, ngroups);
     HIPCHK(c, launch_gemm(c, a, ngroups, swiglu));
   }
   // 5. FFN out + residual
@@ -278,7 +280,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
       G.W[0] = w.w_out; G.B[0] = bias ? w.b_out : nullptr; G.M = rg[g].M;
     }
     a.K = F; a.N[0] = dm; a.ntot = dm; a.ldx = F; a.ldy = dm; a.norm = -1; a.act = 0;
-    ProfScope ps(c, PPD_KC_GEMM_FFN_OUT);
+    ProfScope ps(c, PPD_KC_GEMM_FFN_OUT, ngroups);
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   const uint64_t wl = ((uint64_t)4 * dm * dm + (uint64_t)(d.act == 2 ? 3 : 2) * dm * F) * c->wbytes;
@@ -416,6 +418,8 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   }
   if (e == hipSuccess) e = hipMemset(c->ds, 0, sizeof(DevState));
   if (e != hipSuccess) {
+    g_create_hip_error = (int)e;
+    (void)hipGetLastError();
     free_all(c);
     int rc = (e == hipErrorOutOfMemory) ? PPD_ENOMEM : PPD_EHIP;
     delete c;
@@ -473,18 +477,24 @@ int ppd_step(ppd_ctx* c, int32_t* out_tokens, int max_out, ppd_step_info* info) 
   } else {
     from = nb;   // layers 1..d-dbar were run by the matching candidate row
   }
-  for (int l = from; l < dbar; ++l) {
-    RowGroup g{l, 1, 0, pos, false};
-    if ((rc = run_layer(c, 1, &g))) return rc;
+  if (from < dbar) {
+    ProfScope phase(c, PPD_KC_PHASE, 1);
+    for (int l = from; l < dbar; ++l) {
+      RowGroup g{l, 1, 0, pos, false};
+      if ((rc = run_layer(c, 1, &g))) return rc;
+    }
   }
   c->st.main_layer_rows += dbar - from;
   // early prediction; the candidates become rows 1..k at position pos+1
   if ((rc = run_head(c, true))) return rc;
   if ((rc = run_embed(c, c->ds->cand, k, 1, pos + 1))) return rc;
   // parallel phase: step j runs the main row at layer dbar+j and the candidates at layer j
-  for (int j = 0; j < nb; ++j) {
-    RowGroup g[2] = {{dbar + j, 1, 0, pos, false}, {j, k, 1, pos + 1, true}};
-    if ((rc = run_layer(c, 2, g))) return rc;
+  {
+    ProfScope phase(c, PPD_KC_PHASE, 2);
+    for (int j = 0; j < nb; ++j) {
+      RowGroup g[2] = {{dbar + j, 1, 0, pos, false}, {j, k, 1, pos + 1, true}};
+      if ((rc = run_layer(c, 2, g))) return rc;
+    }
   }
   c->st.main_layer_rows += nb;
   c->st.branch_layer_rows += (uint64_t)k * nb;
@@ -569,10 +579,11 @@ int ppd_set_profiling(ppd_ctx* c, int on) {
   return PPD_OK;
 }
 
-int ppd_get_kernel_time(ppd_ctx* c, int kernel_class, double* ms_total, uint64_t* launches) {
-  if (!c || kernel_class < 0 || kernel_class >= PPD_KC_COUNT || !ms_total || !launches) return PPD_EINVAL;
-  *ms_total = c->kc_ms[kernel_class];
-  *launches = c->kc_n[kernel_class];
+int ppd_get_kernel_time(ppd_ctx* c, int kernel_class, int groups, double* ms_total, uint64_t* launches) {
+  if (!c || kernel_class < 0 || kernel_class >= PPD_KC_COUNT || groups < 1 || groups > 2 || !ms_total || !launches)
+    return PPD_EINVAL;
+  *ms_total = c->kc_ms[kernel_class + (groups - 1) * PPD_KC_COUNT];
+  *launches = c->kc_n[kernel_class + (groups - 1) * PPD_KC_COUNT];
   return PPD_OK;
 }
 
@@ -595,6 +606,6 @@ const char* ppd_strerror(int code) {
   }
 }
 
-int ppd_last_hip_error(const ppd_ctx* c) { return c ? c->last_hip : 0; }
+int ppd_last_hip_error(const ppd_ctx* c) { return c ? c->last_hip : g_create_hip_error; }
 
 }  // extern "C"
