@@ -110,8 +110,10 @@ enum {
   PPD_KC_GEMM_FFN_IN,  /* norm + first FFN matrix (both matrices for SwiGLU) + activation */
   PPD_KC_GEMM_FFN_OUT, /* second FFN matrix + residual */
   PPD_KC_HEAD,       /* final norm + LM head */
-  PPD_KC_SELECT,     /* top-k / arg max / verification */
-  PPD_KC_COMMIT,     /* adoption of the matching candidate: hidden row + KV tail -> cache */
+  PPD_KC_SELECT,     /* merge of the head's block top-k; early: candidates + their embedding rows;
+                        final: arg max, verification, adoption of the matching candidate
+                        (hidden row + KV tails -> cache) */
+  PPD_KC_COMMIT,     /* unused (adoption runs inside PPD_KC_SELECT) */
   PPD_KC_PHASE,      /* not a kernel: one bracket around a whole phase of a round (groups = 1: the
                         main token alone up to the exit layer; groups = 2: the d-dbar pipelined steps) */
   PPD_KC_COUNT
@@ -167,6 +169,9 @@ int ppd_get_stats(const ppd_ctx *ctx, ppd_stats *out);
  * rows), the summed elapsed milliseconds and the number of launches since
  * profiling was enabled (HOST outputs).  Prefill is never profiled. */
 int ppd_set_profiling(ppd_ctx *ctx, int on);
+/* Rounds are replayed as captured HIP graphs (one per round shape) unless profiling is on;
+ * on = 0 issues every launch eagerly instead.  Results are identical either way. */
+int ppd_set_graphs(ppd_ctx *ctx, int on);
 int ppd_get_kernel_time(ppd_ctx *ctx, int kernel_class, int groups, double *ms_total, uint64_t *launches);
 
 void ppd_destroy(ppd_ctx *ctx);

@@ -50,7 +50,8 @@ class Stats(ctypes.Structure):
 
 
 EXPORTS = ("ppd_create", "ppd_reset", "ppd_prefill", "ppd_step", "plain_greedy_step", "ppd_get_logits",
-           "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_get_kernel_time", "ppd_destroy",
+           "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_set_graphs", "ppd_get_kernel_time",
+           "ppd_destroy",
            "ppd_strerror", "ppd_last_hip_error")
 
 _lib = None
@@ -78,6 +79,7 @@ def load_library() -> ctypes.CDLL:
     lib.ppd_get_early_logits.argtypes = [vp, vp]
     lib.ppd_get_stats.argtypes = [vp, ctypes.POINTER(Stats)]
     lib.ppd_set_profiling.argtypes = [vp, ci]
+    lib.ppd_set_graphs.argtypes = [vp, ci]
     lib.ppd_get_kernel_time.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
     lib.ppd_destroy.argtypes = [vp]
     lib.ppd_destroy.restype = None
@@ -198,6 +200,9 @@ class PPD:
 
     def ppd_set_profiling(self, on: bool):
         self._chk(load_library().ppd_set_profiling(self._h, int(on)), "ppd_set_profiling")
+
+    def ppd_set_graphs(self, on: bool):
+        self._chk(load_library().ppd_set_graphs(self._h, int(on)), "ppd_set_graphs")
 
     def ppd_get_kernel_time(self) -> Dict[str, Dict[str, float]]:
         out = {}

@@ -19,19 +19,14 @@ struct LayerW {
   const void *ln1_g, *ln1_b, *wq, *wk, *wv, *wo, *bq, *bk, *bv, *bo, *ln2_g, *ln2_b, *w_in, *w_up, *w_out, *b_in, *b_out;
 };
 
-struct DevState {   // DEVICE ints written by the selection kernels
-  int32_t next_tok; // token the next main row embeds (x_t)
-  int32_t result[2];// token, match_idx of the last final selection
-  int32_t cand[MAXM];
-  int32_t prompt_tok; // scratch id for prefill
-};
-
 }  // namespace
 
 struct ppd_ctx {
   ppd_model_dims d;
   int k, dbar, nb;   // nb = d - dbar: layers each candidate runs, = pipelined steps per round
-  hipStream_t stream;
+  hipStream_t user_stream;   // the caller's stream: work of a call is ordered after what it holds
+  hipStream_t stream;        // the context's own stream: every launch goes here (a graph cannot be captured on the null stream)
+  hipEvent_t join_ev;
   int wbytes;
   // weights (borrowed)
   const void *tok_emb, *pos_emb, *lnf_g, *lnf_b, *lm_head, *early_head;
@@ -45,10 +40,18 @@ struct ppd_ctx {
   float *ffn;            // [1+k][d_ff]
   float *part;           // [1+k][H][nchunk_max][hd+2]
   float *logits, *early_logits;  // [vocab]
+  float *pk_val; int32_t *pk_idx; // [head_grid][MAXM] block top-k candidates of the head GEMM
+  int head_grid;
   float2 *rope;          // [max_ctx][hd/2]
   DevState *ds;
   int32_t *prompt_dev;   // [max_ctx]
   int32_t *host_result;  // pinned, 2 ints
+  int32_t *host_result_dev; // the same memory as the GPU sees it
+  // captured rounds: 0 ppd round from layer 1, 1 ppd round after a match, 2 plain step
+  int use_graphs;
+  hipGraphExec_t graph[3];
+  int graph_chunks[3];   // attention grid (128-position chunks) each graph was captured with
+  int gmax1, gmax2;      // workgroup budget of a GEMM launch: one group / per group of a two-group launch
   int nchunk_max;
   // round state
   int n_ctx;      // absolute position of the pending token x_t (-1: no prefill yet)
@@ -122,21 +125,37 @@ hipError_t launch_gemm_t(ppd_ctx* c, const GemmArgs& a, int ngroups, int MB, dim
   return hipGetLastError();
 }
 
+// Workgroups per group for a GEMM with `nsets` row sets: each workgroup has four waves and every
+// wave takes ceil(nsets / waves) sets, so pick the count in [gmax/2, gmax] that wastes the fewest
+// wave slots (ties: the larger grid).
+int pick_grid(int nsets, int gmax) {
+  int need = (nsets + GEMM_WAVES - 1) / GEMM_WAVES;
+  if (need <= gmax) return need < 1 ? 1 : need;
+  int best = gmax; double best_eff = 0.0;
+  for (int g = gmax; g >= gmax / 2 && g >= 1; --g) {
+    int nw = g * GEMM_WAVES, nit = (nsets + nw - 1) / nw;
+    double eff = (double)nsets / ((double)nit * nw);
+    if (eff > best_eff + 1e-9) { best_eff = eff; best = g; }
+  }
+  return best;
+}
+
 // one skinny GEMM launch; group 0 is always one row, group 1 (optional) has MB rows
 hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
   const int vec = 16 / c->wbytes;
-  const int blk = WAVE * vec;
-  int mmax = ngroups == 2 ? (a.g[1].M > 1 ? a.g[1].M : 1) : 1;
-  int kc_cap = (int)((60 * 1024) / (mmax * sizeof(float))) / blk * blk;
-  int kpad = (a.K + blk - 1) / blk * blk;
+  const int span = GEMM_NB * WAVE * vec;
+  const int mmax = ngroups == 2 ? (a.g[1].M > 1 ? a.g[1].M : 1) : 1;
+  int kc_cap = (int)((60 * 1024) / (mmax * sizeof(float))) / span * span;
+  if (kc_cap < span) kc_cap = span;
+  const int kpad = (a.K + span - 1) / span * span;
   a.KC = kpad < kc_cap ? kpad : kc_cap;
-  int rows_per_tile = GEMM_WAVES * (paired ? GEMM_WROWS / 2 : GEMM_WROWS);
-  a.ntiles = (a.ntot + rows_per_tile - 1) / rows_per_tile;
-  // K fits one LDS pass: a workgroup loops over several tiles with x staged once; otherwise one tile each
-  int gx = a.ntiles;
-  if (a.KC >= a.K) { int tpw = (a.ntiles + 511) / 512; gx = (a.ntiles + tpw - 1) / tpw; }
+  const int lr = paired ? GEMM_WROWS / 2 : GEMM_WROWS;
+  const int nsets = (a.ntot + lr - 1) / lr;
+  int gx;
+  if (a.topk > 0) gx = c->head_grid;
+  else gx = pick_grid(nsets, ngroups == 2 ? c->gmax2 : c->gmax1);
   dim3 grid(gx, ngroups);
-  size_t lds = 32 * sizeof(float) + (size_t)mmax * a.KC * sizeof(float);
+  size_t lds = (GEMM_LDS_HDR + (size_t)mmax * a.KC + (a.topk > 0 ? HEAD_MAX_ROWS : 0)) * sizeof(float);
   int MB = ngroups == 2 ? a.g[1].M : 0;
   if (c->wbytes == 4) return paired ? launch_gemm_t<float, true>(c, a, ngroups, MB, grid, lds)
                                     : launch_gemm_t<float, false>(c, a, ngroups, MB, grid, lds);
@@ -161,9 +180,9 @@ hipError_t launch_attn_t(ppd_ctx* c, const AttnArgs& a, int ngroups, int MB, dim
   return hipGetLastError();
 }
 
-hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups) {
-  int pmax = a.g[0].p;
-  if (ngroups == 2 && a.g[1].p > pmax) pmax = a.g[1].p;
+// pmax: largest position any row of the launch sits at (host-side bound for the grid; the kernel
+// itself reads the position from the device state and idle chunks return at once)
+hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups, int pmax) {
   dim3 grid(pmax / ATT_CHUNK + 1, a.H, ngroups);
   int MB = ngroups == 2 ? a.g[1].M : 0;
   if (c->wbytes == 4) {
@@ -180,12 +199,13 @@ struct RowGroup {
   int layer;     // 0-based
   int M;
   int row0;      // 0: main row; 1: first candidate row
-  int pos;       // absolute position of the rows' token
+  int pos_off;   // the rows' token sits at position (device state pos) + pos_off
   bool tail;     // own K/V go to the candidate tails (slot = row index) instead of the cache
 };
 
 // One transformer layer for one or two row groups (a pipelined step when two).
-int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
+// pmax: host-side upper bound of the rows' positions (sizes the attention grid only).
+int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
   const ppd_model_dims& d = c->d;
   const int dm = d.d_model, F = d.d_ff;
   const bool bias = d.has_bias != 0;
@@ -219,21 +239,21 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
       if (rg[g].tail) {
         size_t off = (size_t)l * c->k * dm * c->wbytes;
         G.ownK = c->tailK + off; G.ownV = c->tailV + off;
-        G.own_row_stride = dm; G.own_head_stride = d.head_dim;
+        G.own_row_stride = dm; G.own_head_stride = d.head_dim; G.own_cache = 0;
       } else {
-        size_t off = (size_t)l * cache_layer_bytes(c) + (size_t)rg[g].pos * d.head_dim * c->wbytes;
+        size_t off = (size_t)l * cache_layer_bytes(c);
         G.ownK = c->Kc + off; G.ownV = c->Vc + off;
-        G.own_row_stride = 0; G.own_head_stride = (long)d.max_ctx * d.head_dim;
+        G.own_row_stride = 0; G.own_head_stride = (long)d.max_ctx * d.head_dim; G.own_cache = 1;
       }
       G.part = c->part + (size_t)rg[g].row0 * part_row;
-      G.p = rg[g].pos; G.M = rg[g].M;
-      mg.part[g] = G.part; mg.out[g] = c->att + (size_t)rg[g].row0 * dm; mg.p[g] = G.p; mg.M[g] = G.M;
-      c->st.kv_bytes += (uint64_t)2 * rg[g].pos * dm * c->wbytes;
+      G.pos_off = rg[g].pos_off; G.M = rg[g].M;
+      mg.part[g] = G.part; mg.out[g] = c->att + (size_t)rg[g].row0 * dm; mg.pos_off[g] = G.pos_off; mg.M[g] = G.M;
     }
+    a.ds = c->ds; mg.ds = c->ds;
     a.rope = d.pos == 1 ? c->rope : nullptr;
     a.H = d.n_heads; a.d_model = dm; a.max_ctx = d.max_ctx; a.nchunk_max = c->nchunk_max;
     a.scale = 1.0f / sqrtf((float)d.head_dim);
-    { ProfScope ps(c, PPD_KC_ATTN, ngroups); HIPCHK(c, launch_attn(c, a, ngroups)); }
+    { ProfScope ps(c, PPD_KC_ATTN, ngroups); HIPCHK(c, launch_attn(c, a, ngroups, pmax)); }
     mg.H = d.n_heads; mg.HD = d.head_dim; mg.d_model = dm; mg.nchunk_max = c->nchunk_max;
     int mmax = rg[0].M; if (ngroups == 2 && rg[1].M > mmax) mmax = rg[1].M;
     ProfScope ps(c, PPD_KC_ATTN_MERGE, ngroups);
@@ -283,15 +303,18 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg) {
     ProfScope ps(c, PPD_KC_GEMM_FFN_OUT, ngroups);
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
-  const uint64_t wl = ((uint64_t)4 * dm * dm + (uint64_t)(d.act == 2 ? 3 : 2) * dm * F) * c->wbytes;
-  c->st.weight_bytes += wl * ngroups;
   return PPD_OK;
 }
 
-int run_embed(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos) {
+EmbedArgs embed_args(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos_off) {
   EmbedArgs a;
-  a.tok_emb = c->tok_emb; a.pos_emb = c->d.pos == 0 ? c->pos_emb : nullptr; a.ids = ids_dev;
-  a.h = c->h + (size_t)row0 * c->d.d_model; a.rows = rows; a.d_model = c->d.d_model; a.pos = pos;
+  a.tok_emb = c->tok_emb; a.pos_emb = c->d.pos == 0 ? c->pos_emb : nullptr; a.ids = ids_dev; a.ds = c->ds;
+  a.h = c->h + (size_t)row0 * c->d.d_model; a.rows = rows; a.d_model = c->d.d_model; a.pos_off = pos_off;
+  return a;
+}
+
+int run_embed(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos_off) {
+  EmbedArgs a = embed_args(c, ids_dev, rows, row0, pos_off);
   dim3 grid((c->d.d_model + 255) / 256, rows);
   ProfScope ps(c, PPD_KC_EMBED);
   if (c->wbytes == 4) hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, c->stream, a);
@@ -300,8 +323,16 @@ int run_embed(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos) {
   return PPD_OK;
 }
 
-// final norm + LM head on the main row, then selection
-int run_head(ppd_ctx* c, bool early) {
+int set_state(ppd_ctx* c, int pos, int tok) {
+  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->stream, c->ds, pos, tok);
+  HIPCHK(c, hipGetLastError());
+  return PPD_OK;
+}
+
+// Final norm + LM head on the main row with every workgroup's own top-k, then the selection
+// kernel.  early: top-k -> candidates, which it also embeds as rows 1..k at the next position.
+// final: arg max, verification; with adopt, the matching candidate's row and KV tails are adopted.
+int run_head(ppd_ctx* c, bool early, bool adopt) {
   const ppd_model_dims& d = c->d;
   {
     GemmArgs a; memset(&a, 0, sizeof a);
@@ -311,32 +342,134 @@ int run_head(ppd_ctx* c, bool early) {
     G.ng = c->lnf_g; G.nb = d.norm == 0 ? c->lnf_b : nullptr; G.M = 1;
     a.K = d.d_model; a.N[0] = d.vocab; a.ntot = d.vocab; a.ldx = d.d_model; a.ldy = d.vocab;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
+    a.topk = early ? c->k : 1; a.pk_val = c->pk_val; a.pk_idx = c->pk_idx;
     ProfScope ps(c, PPD_KC_HEAD);
     HIPCHK(c, launch_gemm(c, a, 1, false));
-    c->st.weight_bytes += (uint64_t)d.vocab * d.d_model * c->wbytes;
   }
-  SelectArgs s;
-  s.logits = early ? c->early_logits : c->logits; s.vocab = d.vocab; s.k = c->k; s.mode = early ? 0 : 1;
-  s.cand = c->ds->cand; s.result = c->ds->result; s.next_tok = &c->ds->next_tok;
+  SelectArgs s; memset(&s, 0, sizeof s);
+  s.pk_val = c->pk_val; s.pk_idx = c->pk_idx; s.nblk = c->head_grid; s.kk = early ? c->k : 1;
+  s.k = adopt || early ? c->k : 0; s.mode = early ? 0 : 1; s.ds = c->ds; s.host_result = c->host_result_dev;
+  dim3 grid(1, 1);
+  if (early) {
+    s.emb = embed_args(c, nullptr, c->k, 1, 1);
+    grid = dim3((d.d_model + SEL_THREADS - 1) / SEL_THREADS, c->k);
+  } else if (adopt) {
+    s.h = c->h; s.tailK = c->tailK; s.tailV = c->tailV; s.Kc = c->Kc; s.Vc = c->Vc;
+    s.nb = c->nb; s.H = d.n_heads; s.hd = d.head_dim; s.d_model = d.d_model; s.max_ctx = d.max_ctx; s.wbytes = c->wbytes;
+    grid = dim3(c->nb, 2);
+  }
   ProfScope ps(c, PPD_KC_SELECT);
-  hipLaunchKernelGGL(select_kernel, dim3(1), dim3(SEL_THREADS), 0, c->stream, s);
+  if (c->wbytes == 4) hipLaunchKernelGGL(select_kernel<float>, grid, dim3(SEL_THREADS), 0, c->stream, s);
+  else hipLaunchKernelGGL(select_kernel<bf16_t>, grid, dim3(SEL_THREADS), 0, c->stream, s);
   HIPCHK(c, hipGetLastError());
   return PPD_OK;
 }
 
-int fetch_result(ppd_ctx* c) {
-  HIPCHK(c, hipMemcpyAsync(c->host_result, c->ds->result, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+// The launches of one round.  kind 0: PPD round from layer 1 (after a miss or a prefill);
+// kind 1: PPD round after a match (layers 1..d-dbar were run by the matching candidate row);
+// kind 2: plain greedy step.  pmax bounds the positions touched (attention grid size only).
+int issue_round(ppd_ctx* c, int kind, int pmax) {
+  const int d = c->d.n_layers, dbar = c->dbar, nb = c->nb, k = c->k;
+  int rc;
+  if (kind == 2) {
+    if ((rc = run_embed(c, &c->ds->next_tok, 1, 0, 0))) return rc;
+    for (int l = 0; l < d; ++l) {
+      RowGroup g{l, 1, 0, 0, false};
+      if ((rc = run_layer(c, 1, &g, pmax))) return rc;
+    }
+    return run_head(c, false, false);
+  }
+  // main token up to the exit layer
+  int from = kind == 1 ? nb : 0;
+  if (kind == 0 && (rc = run_embed(c, &c->ds->next_tok, 1, 0, 0))) return rc;
+  if (from < dbar) {
+    ProfScope phase(c, PPD_KC_PHASE, 1);
+    for (int l = from; l < dbar; ++l) {
+      RowGroup g{l, 1, 0, 0, false};
+      if ((rc = run_layer(c, 1, &g, pmax))) return rc;
+    }
+  }
+  // early prediction; the candidates become rows 1..k at the next position
+  if ((rc = run_head(c, true, false))) return rc;
+  // parallel phase: step j runs the main row at layer dbar+j and the candidates at layer j
+  {
+    ProfScope phase(c, PPD_KC_PHASE, 2);
+    for (int j = 0; j < nb; ++j) {
+      RowGroup g[2] = {{dbar + j, 1, 0, 0, false}, {j, k, 1, 1, true}};
+      if ((rc = run_layer(c, 2, g, pmax))) return rc;
+    }
+  }
+  // final prediction, verification, adoption
+  return run_head(c, false, true);
+}
+
+// Run one round: set the device state, replay (or capture, or issue eagerly) the launches,
+// wait, read token and match index from pinned memory.
+int run_round(ppd_ctx* c, int kind, int pos) {
+  int rc;
+  HIPCHK(c, hipEventRecord(c->join_ev, c->user_stream));
+  HIPCHK(c, hipStreamWaitEvent(c->stream, c->join_ev, 0));
+  if ((rc = set_state(c, pos, -1))) return rc;
+  const int pmax = pos + (kind == 2 ? 0 : 1);
+  if (c->use_graphs && !c->prof) {
+    const int nchunks = pmax / ATT_CHUNK + 1;
+    if (c->graph[kind] && c->graph_chunks[kind] < nchunks) {
+      HIPCHK(c, hipGraphExecDestroy(c->graph[kind]));
+      c->graph[kind] = nullptr;
+    }
+    if (!c->graph[kind]) {
+      // capture with the attention grid sized for the whole 128-position chunk this round ends in
+      hipGraph_t g = nullptr;
+      HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed));
+      rc = issue_round(c, kind, nchunks * ATT_CHUNK - 1);
+      hipError_t e = hipStreamEndCapture(c->stream, &g);
+      if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+      HIPCHK(c, e);
+      e = hipGraphInstantiate(&c->graph[kind], g, nullptr, nullptr, 0);
+      (void)hipGraphDestroy(g);
+      HIPCHK(c, e);
+      c->graph_chunks[kind] = nchunks;
+    }
+    HIPCHK(c, hipGraphLaunch(c->graph[kind], c->stream));
+  } else {
+    if ((rc = issue_round(c, kind, pmax))) return rc;
+  }
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if (c->prof) prof_collect(c);
   return PPD_OK;
 }
 
+void account_round(ppd_ctx* c, int kind, int pos) {
+  const ppd_model_dims& d = c->d;
+  const uint64_t wl = ((uint64_t)4 * d.d_model * d.d_model + (uint64_t)(d.act == 2 ? 3 : 2) * d.d_model * d.d_ff) * c->wbytes;
+  const uint64_t wh = (uint64_t)d.vocab * d.d_model * c->wbytes;
+  const uint64_t kvp = (uint64_t)2 * d.d_model * c->wbytes;     // K and V of one position of one layer
+  if (kind == 2) {
+    c->st.weight_bytes += d.n_layers * wl + wh;
+    c->st.kv_bytes += (uint64_t)d.n_layers * pos * kvp;
+    return;
+  }
+  const int solo = c->dbar - (kind == 1 ? c->nb : 0);
+  c->st.weight_bytes += (uint64_t)(solo + 2 * c->nb) * wl + 2 * wh;
+  c->st.kv_bytes += (uint64_t)(solo + c->nb) * pos * kvp + (uint64_t)c->nb * (pos + 1) * kvp;
+}
+
 void free_all(ppd_ctx* c) {
+  for (int i = 0; i < 3; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
-                 c->early_logits, c->rope, c->ds, c->prompt_dev};
+                 c->early_logits, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  if (c->join_ev) (void)hipEventDestroy(c->join_ev);
+  if (c->stream) (void)hipStreamDestroy(c->stream);
+}
+
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  if (!v || !*v) return dflt;
+  int x = atoi(v);
+  return x > 0 ? x : dflt;
 }
 
 }  // namespace
@@ -370,7 +503,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   ppd_ctx* c = new (std::nothrow) ppd_ctx();
   if (!c) return PPD_ENOMEM;
   c->d = d; c->k = k; c->dbar = exit_layer; c->nb = d.n_layers - exit_layer;
-  c->stream = (hipStream_t)hip_stream;
+  c->user_stream = (hipStream_t)hip_stream;
   c->wbytes = d.wdtype == 0 ? 4 : 2;
   c->tok_emb = w->tok_emb; c->pos_emb = w->pos_emb; c->lnf_g = w->lnf_g; c->lnf_b = w->lnf_b;
   c->lm_head = w->lm_head; c->early_head = w->early_head;
@@ -387,6 +520,18 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   }
   c->nchunk_max = (d.max_ctx + ATT_CHUNK - 1) / ATT_CHUNK;
   c->n_ctx = -1;
+  c->use_graphs = env_int("PPD_GRAPHS", 1) != 2;      // PPD_GRAPHS=2 switches graph replay off
+  c->gmax1 = env_int("PPD_GMAX1", 512);
+  c->gmax2 = env_int("PPD_GMAX2", 256);
+  // head GEMM: as many workgroups as a plain GEMM, more if a workgroup would otherwise
+  // produce over HEAD_MAX_ROWS logits
+  {
+    const int nsets = (d.vocab + GEMM_WROWS - 1) / GEMM_WROWS;
+    int g = pick_grid(nsets, c->gmax1);
+    const int sets_per_wg_cap = HEAD_MAX_ROWS / GEMM_WROWS;      // per workgroup, all four waves together
+    while (((nsets + g * GEMM_WAVES - 1) / (g * GEMM_WAVES)) * GEMM_WAVES > sets_per_wg_cap) ++g;
+    c->head_grid = g;
+  }
   const size_t dm = d.d_model, R = 1 + k;
   hipError_t e = hipSuccess;
   auto alloc = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
@@ -401,10 +546,15 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   alloc((void**)&c->part, R * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
   alloc((void**)&c->logits, (size_t)d.vocab * sizeof(float));
   alloc((void**)&c->early_logits, (size_t)d.vocab * sizeof(float));
+  alloc((void**)&c->pk_val, (size_t)c->head_grid * MAXM * sizeof(float));
+  alloc((void**)&c->pk_idx, (size_t)c->head_grid * MAXM * sizeof(int32_t));
   alloc((void**)&c->ds, sizeof(DevState));
   alloc((void**)&c->prompt_dev, (size_t)d.max_ctx * sizeof(int32_t));
   if (d.pos == 1) alloc((void**)&c->rope, (size_t)d.max_ctx * (d.head_dim / 2) * sizeof(float2));
-  if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, 2 * sizeof(int32_t), hipHostMallocDefault);
+  if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, 2 * sizeof(int32_t), hipHostMallocMapped);
+  if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&c->host_result_dev, c->host_result, 0);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
   if (e == hipSuccess && d.pos == 1) {
     // (cos, sin) of pos * theta^(-2i/hd), evaluated in double on the host
     const int half = d.head_dim / 2;
@@ -444,20 +594,23 @@ int ppd_prefill(ppd_ctx* c, const int32_t* prompt, int n_prompt) {
     if (prompt[i] < 0 || prompt[i] >= c->d.vocab) return PPD_EINVAL;
   int rc = ppd_reset(c);
   if (rc) return rc;
+  HIPCHK(c, hipEventRecord(c->join_ev, c->user_stream));
+  HIPCHK(c, hipStreamWaitEvent(c->stream, c->join_ev, 0));
   HIPCHK(c, hipMemcpyAsync(c->prompt_dev, prompt, (size_t)n_prompt * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));   // prompt is pageable host memory of the caller
   int prof = c->prof; c->prof = 0;
-  for (int i = 0; i + 1 < n_prompt; ++i) {
-    if ((rc = run_embed(c, c->prompt_dev + i, 1, 0, i))) { c->prof = prof; return rc; }
-    for (int l = 0; l < c->d.n_layers; ++l) {
-      RowGroup g{l, 1, 0, i, false};
-      if ((rc = run_layer(c, 1, &g))) { c->prof = prof; return rc; }
+  for (int i = 0; i + 1 < n_prompt && !rc; ++i) {
+    rc = set_state(c, i, -1);
+    if (!rc) rc = run_embed(c, c->prompt_dev + i, 1, 0, 0);
+    for (int l = 0; l < c->d.n_layers && !rc; ++l) {
+      RowGroup g{l, 1, 0, 0, false};
+      rc = run_layer(c, 1, &g, i);
     }
   }
   c->prof = prof;
-  HIPCHK(c, hipMemcpyAsync(&c->ds->next_tok, c->prompt_dev + (n_prompt - 1), sizeof(int32_t), hipMemcpyDeviceToDevice, c->stream));
+  if (rc) return rc;
+  if ((rc = set_state(c, n_prompt - 1, prompt[n_prompt - 1]))) return rc;
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  memset(&c->st, 0, sizeof c->st);
   c->n_ctx = n_prompt - 1; c->matched = 0; c->finished = 0;
   return PPD_OK;
 }
@@ -466,51 +619,16 @@ int ppd_step(ppd_ctx* c, int32_t* out_tokens, int max_out, ppd_step_info* info) 
   if (!c || !out_tokens || max_out < 1) return PPD_EINVAL;
   if (c->n_ctx < 0) return PPD_ESTATE;
   if (c->finished) return 0;
-  const int pos = c->n_ctx, d = c->d.n_layers, dbar = c->dbar, nb = c->nb, k = c->k;
+  const int pos = c->n_ctx;
   if (pos + 1 >= c->d.max_ctx) return PPD_ECTX;   // the candidates sit at position pos+1
-  int rc;
-  // main token up to the exit layer
-  int from = 0;
-  if (!c->matched) {
-    if ((rc = run_embed(c, &c->ds->next_tok, 1, 0, pos))) return rc;
-    c->st.runs += 1;
-  } else {
-    from = nb;   // layers 1..d-dbar were run by the matching candidate row
-  }
-  if (from < dbar) {
-    ProfScope phase(c, PPD_KC_PHASE, 1);
-    for (int l = from; l < dbar; ++l) {
-      RowGroup g{l, 1, 0, pos, false};
-      if ((rc = run_layer(c, 1, &g))) return rc;
-    }
-  }
-  c->st.main_layer_rows += dbar - from;
-  // early prediction; the candidates become rows 1..k at position pos+1
-  if ((rc = run_head(c, true))) return rc;
-  if ((rc = run_embed(c, c->ds->cand, k, 1, pos + 1))) return rc;
-  // parallel phase: step j runs the main row at layer dbar+j and the candidates at layer j
-  {
-    ProfScope phase(c, PPD_KC_PHASE, 2);
-    for (int j = 0; j < nb; ++j) {
-      RowGroup g[2] = {{dbar + j, 1, 0, pos, false}, {j, k, 1, pos + 1, true}};
-      if ((rc = run_layer(c, 2, g))) return rc;
-    }
-  }
-  c->st.main_layer_rows += nb;
-  c->st.branch_layer_rows += (uint64_t)k * nb;
-  // final prediction, verification, adoption
-  if ((rc = run_head(c, false))) return rc;
-  {
-    CommitArgs a;
-    a.result = c->ds->result; a.h = c->h; a.tailK = c->tailK; a.tailV = c->tailV; a.Kc = c->Kc; a.Vc = c->Vc;
-    a.k = k; a.H = c->d.n_heads; a.hd = c->d.head_dim; a.d_model = c->d.d_model; a.max_ctx = c->d.max_ctx;
-    a.pos_next = pos + 1; a.wbytes = c->wbytes;
-    ProfScope ps(c, PPD_KC_COMMIT);
-    hipLaunchKernelGGL(commit_kernel, dim3(nb, 2), dim3(256), 0, c->stream, a);
-    HIPCHK(c, hipGetLastError());
-  }
-  if ((rc = fetch_result(c))) return rc;
+  const int kind = c->matched ? 1 : 0;
+  int rc = run_round(c, kind, pos);
+  if (rc) return rc;
+  account_round(c, kind, pos);
   const int tok = c->host_result[0], midx = c->host_result[1];
+  if (kind == 0) c->st.runs += 1;
+  c->st.main_layer_rows += (uint64_t)(c->dbar - (kind == 1 ? c->nb : 0)) + c->nb;
+  c->st.branch_layer_rows += (uint64_t)c->k * c->nb;
   c->n_ctx = pos + 1;
   c->matched = midx >= 0;
   c->have_early = 1;
@@ -522,9 +640,8 @@ int ppd_step(ppd_ctx* c, int32_t* out_tokens, int max_out, ppd_step_info* info) 
     info->token = tok; info->matched = c->matched; info->match_idx = midx;
     int32_t cand[MAXM];
     HIPCHK(c, hipMemcpy(cand, c->ds->cand, sizeof cand, hipMemcpyDeviceToHost));
-    for (int i = 0; i < PPD_MAX_K; ++i) info->cand[i] = i < k ? cand[i] : -1;
+    for (int i = 0; i < PPD_MAX_K; ++i) info->cand[i] = i < c->k ? cand[i] : -1;
   }
-  (void)d;
   return 1;
 }
 
@@ -534,14 +651,9 @@ int plain_greedy_step(ppd_ctx* c, int32_t* out_token) {
   if (c->finished) return 0;
   const int pos = c->n_ctx;
   if (pos >= c->d.max_ctx) return PPD_ECTX;
-  int rc;
-  if ((rc = run_embed(c, &c->ds->next_tok, 1, 0, pos))) return rc;
-  for (int l = 0; l < c->d.n_layers; ++l) {
-    RowGroup g{l, 1, 0, pos, false};
-    if ((rc = run_layer(c, 1, &g))) return rc;
-  }
-  if ((rc = run_head(c, false))) return rc;
-  if ((rc = fetch_result(c))) return rc;
+  int rc = run_round(c, 2, pos);
+  if (rc) return rc;
+  account_round(c, 2, pos);
   c->n_ctx = pos + 1;
   c->matched = 0;
   c->st.plain_steps += 1;
@@ -579,6 +691,12 @@ int ppd_set_profiling(ppd_ctx* c, int on) {
   return PPD_OK;
 }
 
+int ppd_set_graphs(ppd_ctx* c, int on) {
+  if (!c) return PPD_EINVAL;
+  c->use_graphs = on ? 1 : 0;
+  return PPD_OK;
+}
+
 int ppd_get_kernel_time(ppd_ctx* c, int kernel_class, int groups, double* ms_total, uint64_t* launches) {
   if (!c || kernel_class < 0 || kernel_class >= PPD_KC_COUNT || groups < 1 || groups > 2 || !ms_total || !launches)
     return PPD_EINVAL;
@@ -589,7 +707,7 @@ int ppd_get_kernel_time(ppd_ctx* c, int kernel_class, int groups, double* ms_tot
 
 void ppd_destroy(ppd_ctx* c) {
   if (!c) return;
-  (void)hipStreamSynchronize(c->stream);
+  if (c->stream) (void)hipStreamSynchronize(c->stream);
   free_all(c);
   delete c;
 }

@@ -8,11 +8,12 @@
 //
 // Bit-reproducibility rule: the arithmetic that produces one output row
 // depends only on that row's inputs, never on how many rows share the launch,
-// on the group, or on where the row's own key/value is stored.  Each reduction
-// has one fixed order (lane -> k mapping, butterfly across lanes, waves in
-// index order, position chunks in index order), and every multiply-add is an
-// explicit fmaf.  This is what makes a candidate row's layers 1..d-dbar equal,
-// bit for bit, to the layers plain decoding would run on the same token.
+// on the group, on the grid, or on where the row's own key/value is stored.
+// Each reduction has one fixed order (lane -> k mapping, butterfly across
+// lanes, waves in index order, position chunks in index order), and every
+// multiply-add is an explicit fmaf.  This is what makes a candidate row's
+// layers 1..d-dbar equal, bit for bit, to the layers plain decoding would run
+// on the same token.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -20,15 +21,28 @@
 namespace ppd {
 
 struct bf16_t { uint16_t v; };
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int WAVE = 64;
 constexpr int GEMM_THREADS = 256;   // 4 waves
 constexpr int GEMM_WAVES = GEMM_THREADS / WAVE;
-constexpr int GEMM_WROWS = 4;       // weight rows per wave per tile
+constexpr int GEMM_WROWS = 4;       // weight rows a wave streams together
+constexpr int GEMM_NB = 2;          // k-blocks (64 lanes x 16 bytes each) per register batch
+constexpr int GEMM_LDS_HDR = 96;    // floats in front of the x tile: norm statistics and their reduction scratch
+constexpr int HEAD_MAX_ROWS = 256;  // logits one workgroup of the head GEMM may produce (block top-k buffer)
 constexpr int ATT_THREADS = 256;
 constexpr int ATT_WAVES = ATT_THREADS / WAVE;
 constexpr int ATT_CHUNK = 128;      // positions per workgroup; chunk c covers [c*128, (c+1)*128)
 constexpr int MAXM = 8;
+
+// Round state in device memory, written by the tiny state kernel before a round and by the
+// selection kernels during it; read by every kernel that needs a position or a token id.
+struct DevState {
+  int32_t pos;        // absolute position of the main token x_t
+  int32_t next_tok;   // id of x_t
+  int32_t result[2];  // token x_{t+1}, match_idx of the last final selection
+  int32_t cand[MAXM]; // early top-k ids
+};
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest even
@@ -41,7 +55,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest 
 template <typename WT> struct WTr;
 template <> struct WTr<float> {
   static constexpr int VEC = 4;
-  __device__ static __forceinline__ void unpack(const uint4& r, float* f) {
+  __device__ static __forceinline__ void unpack(const u32x4& r, float* f) {
     f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
   }
   __device__ static __forceinline__ float load1(const void* p, size_t i) { return ((const float*)p)[i]; }
@@ -50,7 +64,7 @@ template <> struct WTr<float> {
 };
 template <> struct WTr<bf16_t> {
   static constexpr int VEC = 8;
-  __device__ static __forceinline__ void unpack(const uint4& r, float* f) {
+  __device__ static __forceinline__ void unpack(const u32x4& r, float* f) {
     f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
     f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
     f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
@@ -60,6 +74,9 @@ template <> struct WTr<bf16_t> {
   __device__ static __forceinline__ float round(float x) { return bf16_to_f32(f32_to_bf16(x)); }
   __device__ static __forceinline__ void store1(void* p, size_t i, float x) { ((uint16_t*)p)[i] = f32_to_bf16(x); }
 };
+
+// weights and cached keys/values are read once per launch: stream them past the caches
+__device__ __forceinline__ u32x4 ld_stream(const void* p) { return __builtin_nontemporal_load((const u32x4*)p); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -71,17 +88,19 @@ __device__ __forceinline__ float wave_max(float v) {
   for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
   return v;
 }
-// Sum over a 256-thread workgroup: butterfly inside each wave, then the four wave
-// sums in index order.  red: >= 4 floats of LDS.  Ends with every thread holding the sum.
-__device__ __forceinline__ float block_sum(float v, float* red) {
-  v = wave_sum(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float s = red[0];
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+// arg max by (value descending, id ascending) over a wave; every lane ends with the winner
+__device__ __forceinline__ void wave_best(float& v, int& i) {
 #pragma unroll
-  for (int w = 1; w < GEMM_WAVES; ++w) s += red[w];
-  return s;
+  for (int o = 32; o >= 1; o >>= 1) {
+    float ov = __shfl_xor(v, o, WAVE); int oi = __shfl_xor(i, o, WAVE);
+    if (better(ov, oi, v, i)) { v = ov; i = oi; }
+  }
+}
+
+// ------------------------------------------------------------------ round state
+__global__ void set_state_kernel(DevState* ds, int pos, int tok) {
+  if (threadIdx.x == 0) { ds->pos = pos; if (tok >= 0) ds->next_tok = tok; }
 }
 
 // ------------------------------------------------------------------ embedding
@@ -89,24 +108,34 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 struct EmbedArgs {
   const void* tok_emb; const void* pos_emb;   // pos_emb null for RoPE models
   const int32_t* ids;   // DEVICE: token id of row r is ids[r]
+  const DevState* ds;
   float* h;             // [rows][d_model]
-  int rows, d_model, pos;
+  int rows, d_model, pos_off;   // the rows sit at position ds->pos + pos_off
 };
 template <typename WT>
-__global__ void embed_kernel(EmbedArgs a) {
-  int r = blockIdx.y;
+__device__ __forceinline__ void embed_rows(const EmbedArgs& a, int r, int i0, int stride) {
   int tok = a.ids[r];
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < a.d_model; i += gridDim.x * blockDim.x) {
+  int pos = a.ds->pos + a.pos_off;
+  for (int i = i0; i < a.d_model; i += stride) {
     float v = WTr<WT>::load1(a.tok_emb, (size_t)tok * a.d_model + i);
-    if (a.pos_emb) v += WTr<WT>::load1(a.pos_emb, (size_t)a.pos * a.d_model + i);
+    if (a.pos_emb) v += WTr<WT>::load1(a.pos_emb, (size_t)pos * a.d_model + i);
     a.h[(size_t)r * a.d_model + i] = v;
   }
+}
+template <typename WT>
+__global__ void embed_kernel(EmbedArgs a) {
+  embed_rows<WT>(a, blockIdx.y, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
 }
 
 // ------------------------------------------------------------------ skinny GEMM
 // Y[m][n] = epilogue( sum_k norm(X)[m][k] * W[n][k] ), M <= 8 rows per group.
 // The layer forward of the main process and of the sub-processes (Algorithm 2);
 // the sub-processes' k rows share one pass over their layer's weights.
+//
+// A workgroup stages its group's (normalised) input rows in LDS once, then its
+// four waves each stream sets of four weight rows with 16-byte non-temporal
+// loads, one register batch ahead of the arithmetic.  The first batch is
+// requested before the input rows are staged.
 struct GemmGroup {
   const float* X;     // [M][ldx] input rows (before the fused norm)
   const float* Rsd;   // residual rows [M][ldy] added in the epilogue, or null
@@ -125,8 +154,9 @@ struct GemmArgs {
   int norm;         // -1 none, 0 LayerNorm, 1 RMSNorm
   float eps;
   int act;          // 0 none, 1 GELU, 2 ReLU, 3 SwiGLU (pairs W[0], W[1])
-  int KC;           // K elements staged in LDS at a time (multiple of 64*VEC)
-  int ntiles;       // tiles per group
+  int KC;           // K elements staged in LDS at a time (multiple of GEMM_NB*64*VEC)
+  int topk;         // > 0: LM-head launch; every workgroup also writes its own top-k (value, id)
+  float* pk_val; int32_t* pk_idx;   // [gridDim.x][MAXM] block candidates (topk > 0)
 };
 
 __device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
@@ -135,64 +165,36 @@ __device__ __forceinline__ float silu(float u) { return u / (1.0f + expf(-u)); }
 template <typename WT, int MT, bool PAIRED>
 __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G, float* lds) {
   constexpr int VEC = WTr<WT>::VEC;
-  constexpr int LR = PAIRED ? GEMM_WROWS / 2 : GEMM_WROWS;  // logical rows per wave
+  constexpr int BK = WAVE * VEC;                 // k elements per block
+  constexpr int SPAN = GEMM_NB * BK;             // k elements per batch
+  constexpr int LR = PAIRED ? GEMM_WROWS / 2 : GEMM_WROWS;  // logical rows per set
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int M = G.M, K = a.K, KC = a.KC;
-  float* red = lds;                 // 8 floats
-  float* stat = lds + 8;            // mu[MAXM], rstd[MAXM]
-  float4* xs4 = (float4*)(lds + 32);  // [M][KC/4] float4, swizzled per 8-group for VEC == 8
+  float* stat = lds;                  // mu[MAXM], rstd[MAXM]
+  float* redA = lds + 16;             // [MAXM][GEMM_WAVES] partial sums
+  float* redB = lds + 48;             // [MAXM][GEMM_WAVES] partial sums of squared deviations
+  float4* xs4 = (float4*)(lds + GEMM_LDS_HDR);  // [MT][KC/4] float4; for VEC == 8 the two halves of every 8-group are split
 
-  // statistics of the fused norm: per row, fixed order
-  if (a.norm >= 0) {
-    for (int m = 0; m < M; ++m) {
-      const float* x = G.X + (size_t)m * a.ldx;
-      float mu = 0.f;
-      if (a.norm == 0) {
-        float s = 0.f;
-        for (int i = tid; i < K; i += GEMM_THREADS) s += x[i];
-        mu = block_sum(s, red) / (float)K;
-      }
-      float s2 = 0.f;
-      for (int i = tid; i < K; i += GEMM_THREADS) { float d = x[i] - mu; s2 = fmaf(d, d, s2); }
-      float var = block_sum(s2, red) / (float)K;
-      if (tid == 0) { stat[m] = mu; stat[MAXM + m] = 1.0f / sqrtf(var + a.eps); }
-    }
-    __syncthreads();
-  }
+  const int nsets = (a.ntot + LR - 1) / LR;
+  const int nwaves = gridDim.x * GEMM_WAVES;
+  const int gw = blockIdx.x * GEMM_WAVES + wave;
+  const int nit = (nsets + nwaves - 1) / nwaves;           // sets per wave, the same count for every wave
+  const int nbps = (K + SPAN - 1) / SPAN;                  // batches per set
+  const int bpc = KC / SPAN;                               // batches per staged chunk
+  const bool single = KC >= K;
+  const int Q = nit * nbps;
 
-  // stage (normalised) x[m][k0 .. k0+kc) in LDS
-  auto stage = [&](int k0, int kc) {
-    for (int idx = tid * 4; idx < M * kc; idx += GEMM_THREADS * 4) {
-      int m = idx / kc, kk = idx - m * kc;
-      float4 v = *(const float4*)(G.X + (size_t)m * a.ldx + k0 + kk);
-      if (a.norm >= 0) {
-        float mu = stat[m], rs = stat[MAXM + m];
-        float xv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float gq = WTr<WT>::load1(G.ng, k0 + kk + e);
-          float t = (xv[e] - mu) * rs * gq;
-          if (G.nb) t += WTr<WT>::load1(G.nb, k0 + kk + e);
-          xv[e] = t;
-        }
-        v = make_float4(xv[0], xv[1], xv[2], xv[3]);
-      }
-      int slot = (VEC == 8) ? (((kk & 7) >> 2) * (KC >> 3) + (kk >> 3)) : (kk >> 2);
-      xs4[m * (KC >> 2) + slot] = v;
-    }
-  };
-  const bool single = KC >= K;   // the whole reduction length fits one LDS pass: stage once
-  bool staged = false;
-
-  for (int tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
-    // the wave's weight rows
-    const char* wp[GEMM_WROWS];
-    int lrow[LR];
+  // ---- load side: one batch ahead
+  const char* wp[GEMM_WROWS];
+  bool lvalid = false;
+  auto set_rows = [&](int it) {
+    int s = gw + it * nwaves;
+    lvalid = s < nsets;
 #pragma unroll
     for (int r = 0; r < LR; ++r) {
-      int n = (tile * GEMM_WAVES + wave) * LR + r;
-      lrow[r] = n;
+      int n = s * LR + r;
       int nc = n < a.ntot ? n : a.ntot - 1;
+      if (nc < 0) nc = 0;
       if (PAIRED) {
         wp[2 * r] = (const char*)G.W[0] + (size_t)nc * K * sizeof(WT);
         wp[2 * r + 1] = (const char*)G.W[1] + (size_t)nc * K * sizeof(WT);
@@ -202,82 +204,210 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G,
         wp[r] = (const char*)G.W[seg] + (size_t)loc * K * sizeof(WT);
       }
     }
-    float acc[GEMM_WROWS][MT];
+  };
+  auto issue = [&](int b, u32x4 (&buf)[GEMM_NB][GEMM_WROWS]) {
 #pragma unroll
-    for (int r = 0; r < GEMM_WROWS; ++r)
+    for (int j = 0; j < GEMM_NB; ++j) {
+      int k = b * SPAN + j * BK + lane * VEC;
+      bool ok = lvalid && k < K;
 #pragma unroll
-      for (int m = 0; m < MT; ++m) acc[r][m] = 0.f;
-
-    for (int k0 = 0; k0 < K; k0 += KC) {
-      const int kc = (K - k0) < KC ? (K - k0) : KC;
-      if (!single || !staged) {
-        __syncthreads();
-        stage(k0, kc);
-        __syncthreads();
-        staged = true;
-      }
-      // stream the weight rows of this chunk
-#pragma unroll 2
-      for (int kb = lane * VEC; kb < kc; kb += WAVE * VEC) {
-        uint4 wv[GEMM_WROWS];
-#pragma unroll
-        for (int r = 0; r < GEMM_WROWS; ++r) wv[r] = *(const uint4*)(wp[r] + (size_t)(k0 + kb) * sizeof(WT));
-        float xf[MT][VEC];
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-          if (m < M) {
-            float4 lo = xs4[m * (KC >> 2) + (VEC == 8 ? (kb >> 3) : (kb >> 2))];
-            xf[m][0] = lo.x; xf[m][1] = lo.y; xf[m][2] = lo.z; xf[m][3] = lo.w;
-            if constexpr (VEC == 8) {
-              float4 hi = xs4[m * (KC >> 2) + (KC >> 3) + (kb >> 3)];
-              xf[m][4] = hi.x; xf[m][5] = hi.y; xf[m][6] = hi.z; xf[m][7] = hi.w;
-            }
-          } else {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) xf[m][e] = 0.f;
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < GEMM_WROWS; ++r) {
-          float wf[VEC];
-          WTr<WT>::unpack(wv[r], wf);
-#pragma unroll
-          for (int m = 0; m < MT; ++m)
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[r][m] = fmaf(xf[m][e], wf[e], acc[r][m]);
-        }
+      for (int r = 0; r < GEMM_WROWS; ++r) {
+        if (ok) buf[j][r] = ld_stream(wp[r] + (size_t)k * sizeof(WT));
+        else buf[j][r] = (u32x4){0u, 0u, 0u, 0u};
       }
     }
-    // cross-lane reduction and epilogue
+  };
+
+  u32x4 bufA[GEMM_NB][GEMM_WROWS], bufB[GEMM_NB][GEMM_WROWS];
+  int l_it = 0, l_b = 0;
+  set_rows(0);
+  issue(0, bufA);
+
+  // ---- stage x rows [k0, k0 + KC) into LDS, normalised when the launch fuses a norm
+  auto stage = [&](int k0) {
+    const int kc = (K - k0) < KC ? (K - k0) : KC;          // valid elements, multiple of VEC (>= 4)
+    for (int idx = tid * 4; idx < M * KC; idx += GEMM_THREADS * 4) {
+      int m = idx / KC, kk = idx - m * KC;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);          // zero tail: weights beyond K are zero too
+      if (kk < kc) {
+        v = *(const float4*)(G.X + (size_t)m * a.ldx + k0 + kk);
+        if (a.norm >= 0) {
+          float mu = stat[m], rs = stat[MAXM + m];
+          float xv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int r = 0; r < GEMM_WROWS; ++r)
-#pragma unroll
-      for (int m = 0; m < MT; ++m) acc[r][m] = wave_sum(acc[r][m]);
-    if (lane == 0) {
-#pragma unroll
-      for (int r = 0; r < LR; ++r) {
-        int n = lrow[r];
-        if (n >= a.ntot) continue;
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-          if (m >= M) continue;
-          float y;
-          if (PAIRED) {
-            float gt = acc[2 * r][m], up = acc[2 * r + 1][m];
-            if (G.B[0]) gt += WTr<WT>::load1(G.B[0], n);
-            if (G.B[1]) up += WTr<WT>::load1(G.B[1], n);
-            y = silu(gt) * up;
-          } else {
-            y = acc[r][m];
-            int seg = 0, loc = n;
-            if (loc >= a.N[0]) { loc -= a.N[0]; seg = 1; if (loc >= a.N[1]) { loc -= a.N[1]; seg = 2; } }
-            if (G.B[seg]) y += WTr<WT>::load1(G.B[seg], loc);
-            if (a.act == 1) y = gelu_erf(y);
-            else if (a.act == 2) y = fmaxf(y, 0.f);
+          for (int e = 0; e < 4; ++e) {
+            float t = (xv[e] - mu) * rs * WTr<WT>::load1(G.ng, k0 + kk + e);
+            if (G.nb) t += WTr<WT>::load1(G.nb, k0 + kk + e);
+            xv[e] = t;
           }
-          if (G.Rsd) y += G.Rsd[(size_t)m * a.ldy + n];
-          G.Y[(size_t)m * a.ldy + n] = y;
+          v = make_float4(xv[0], xv[1], xv[2], xv[3]);
         }
+      }
+      int slot = (VEC == 8) ? (((kk & 7) >> 2) * (KC >> 3) + (kk >> 3)) : (kk >> 2);
+      xs4[m * (KC >> 2) + slot] = v;
+    }
+  };
+
+  // ---- statistics of the fused norm, per row in one fixed order: every thread sums a strided
+  // share of the row (float4 at 4*tid, 4*tid + 1024, ...), butterfly inside each wave, then the
+  // four wave sums in index order.  LayerNorm: mean first, then the squared deviations.
+  if (a.norm >= 0) {
+    if (a.norm == 0) {
+      for (int m = 0; m < M; ++m) {
+        const float* x = G.X + (size_t)m * a.ldx;
+        float s = 0.f;
+        for (int i = tid * 4; i < K; i += GEMM_THREADS * 4) {
+          float4 v = *(const float4*)(x + i);
+          s += v.x; s += v.y; s += v.z; s += v.w;
+        }
+        s = wave_sum(s);
+        if (lane == 0) redA[m * GEMM_WAVES + wave] = s;
+      }
+      __syncthreads();
+    }
+    for (int m = 0; m < M; ++m) {
+      const float* x = G.X + (size_t)m * a.ldx;
+      float mu = 0.f;
+      if (a.norm == 0) mu = (((redA[m * GEMM_WAVES] + redA[m * GEMM_WAVES + 1]) + redA[m * GEMM_WAVES + 2]) + redA[m * GEMM_WAVES + 3]) / (float)K;
+      float s2 = 0.f;
+      for (int i = tid * 4; i < K; i += GEMM_THREADS * 4) {
+        float4 v = *(const float4*)(x + i);
+        float d0 = v.x - mu, d1 = v.y - mu, d2 = v.z - mu, d3 = v.w - mu;
+        s2 = fmaf(d0, d0, s2); s2 = fmaf(d1, d1, s2); s2 = fmaf(d2, d2, s2); s2 = fmaf(d3, d3, s2);
+      }
+      s2 = wave_sum(s2);
+      if (lane == 0) redB[m * GEMM_WAVES + wave] = s2;
+      if (tid == 0) stat[m] = mu;
+    }
+    __syncthreads();
+    if (tid < M) {
+      float var = (((redB[tid * GEMM_WAVES] + redB[tid * GEMM_WAVES + 1]) + redB[tid * GEMM_WAVES + 2]) + redB[tid * GEMM_WAVES + 3]) / (float)K;
+      stat[MAXM + tid] = 1.0f / sqrtf(var + a.eps);
+    }
+    __syncthreads();
+  }
+  if (single) { stage(0); __syncthreads(); }
+
+  float acc[GEMM_WROWS][MT];
+#pragma unroll
+  for (int r = 0; r < GEMM_WROWS; ++r)
+#pragma unroll
+    for (int m = 0; m < MT; ++m) acc[r][m] = 0.f;
+  float* hlog = lds + GEMM_LDS_HDR + (size_t)MT * KC;   // [HEAD_MAX_ROWS] logits of this workgroup (topk launches)
+
+  auto step = [&](int q, u32x4 (&cur)[GEMM_NB][GEMM_WROWS], u32x4 (&nxt)[GEMM_NB][GEMM_WROWS]) {
+    const int c_it = q / nbps, c_b = q - c_it * nbps;
+    // request the next batch
+    if (q + 1 < Q) {
+      if (++l_b == nbps) { l_b = 0; ++l_it; set_rows(l_it); }
+      issue(l_b, nxt);
+    }
+    if (!single && (c_b % bpc) == 0) {
+      __syncthreads();
+      stage(c_b * SPAN);
+      __syncthreads();
+    }
+    const int k0 = single ? 0 : (c_b / bpc) * KC;
+#pragma unroll
+    for (int j = 0; j < GEMM_NB; ++j) {
+      const int kl = c_b * SPAN + j * BK + lane * VEC - k0;    // < KC
+      float xf[MT][VEC];
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        if (m < M) {
+          float4 lo = xs4[m * (KC >> 2) + (VEC == 8 ? (kl >> 3) : (kl >> 2))];
+          xf[m][0] = lo.x; xf[m][1] = lo.y; xf[m][2] = lo.z; xf[m][3] = lo.w;
+          if constexpr (VEC == 8) {
+            float4 hi = xs4[m * (KC >> 2) + (KC >> 3) + (kl >> 3)];
+            xf[m][4] = hi.x; xf[m][5] = hi.y; xf[m][6] = hi.z; xf[m][7] = hi.w;
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) xf[m][e] = 0.f;
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < GEMM_WROWS; ++r) {
+        float wf[VEC];
+        WTr<WT>::unpack(cur[j][r], wf);
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc[r][m] = fmaf(xf[m][e], wf[e], acc[r][m]);
+      }
+    }
+    if (c_b == nbps - 1) {
+      // the set is complete: cross-lane reduction and epilogue
+#pragma unroll
+      for (int r = 0; r < GEMM_WROWS; ++r)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[r][m] = wave_sum(acc[r][m]);
+      const int s = gw + c_it * nwaves;
+      if (lane == 0 && s < nsets) {
+#pragma unroll
+        for (int r = 0; r < LR; ++r) {
+          int n = s * LR + r;
+          if (n >= a.ntot) continue;
+#pragma unroll
+          for (int m = 0; m < MT; ++m) {
+            if (m >= M) continue;
+            float y;
+            if (PAIRED) {
+              float gt = acc[2 * r][m], up = acc[2 * r + 1][m];
+              if (G.B[0]) gt += WTr<WT>::load1(G.B[0], n);
+              if (G.B[1]) up += WTr<WT>::load1(G.B[1], n);
+              y = silu(gt) * up;
+            } else {
+              y = acc[r][m];
+              int seg = 0, loc = n;
+              if (loc >= a.N[0]) { loc -= a.N[0]; seg = 1; if (loc >= a.N[1]) { loc -= a.N[1]; seg = 2; } }
+              if (G.B[seg]) y += WTr<WT>::load1(G.B[seg], loc);
+              if (a.act == 1) y = gelu_erf(y);
+              else if (a.act == 2) y = fmaxf(y, 0.f);
+            }
+            if (G.Rsd) y += G.Rsd[(size_t)m * a.ldy + n];
+            G.Y[(size_t)m * a.ldy + n] = y;
+            if (a.topk > 0 && m == 0) hlog[(c_it * GEMM_WAVES + wave) * LR + r] = y;
+          }
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < GEMM_WROWS; ++r)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[r][m] = 0.f;
+    }
+  };
+  for (int q = 0; q < Q; q += 2) {
+    step(q, bufA, bufB);
+    if (q + 1 < Q) step(q + 1, bufB, bufA);
+  }
+
+  // ---- LM head: this workgroup's top-k by (logit descending, id ascending)
+  if (a.topk > 0) {
+    __syncthreads();
+    if (wave == 0) {
+      // entry e = (it*4 + w)*LR + r  <->  vocabulary id ((blockIdx.x*4 + w) + it*nwaves)*LR + r
+      constexpr int EPL = HEAD_MAX_ROWS / WAVE;
+      float ev[EPL]; int ei[EPL];
+      const int nent = nit * GEMM_WAVES * LR;
+#pragma unroll
+      for (int u = 0; u < EPL; ++u) {
+        int e = lane + u * WAVE;
+        ev[u] = -INFINITY; ei[u] = 0x7fffffff;
+        if (e < nent) {
+          int r = e % LR, t = e / LR, w = t % GEMM_WAVES, it = t / GEMM_WAVES;
+          int id = ((blockIdx.x * GEMM_WAVES + w) + it * nwaves) * LR + r;
+          if (id < a.ntot) { ev[u] = hlog[e]; ei[u] = id; }
+        }
+      }
+      for (int r = 0; r < a.topk; ++r) {
+        float v = -INFINITY; int i = 0x7fffffff;
+#pragma unroll
+        for (int u = 0; u < EPL; ++u) if (better(ev[u], ei[u], v, i)) { v = ev[u]; i = ei[u]; }
+        wave_best(v, i);
+#pragma unroll
+        for (int u = 0; u < EPL; ++u) if (ei[u] == i) { ev[u] = -INFINITY; ei[u] = 0x7fffffff; }
+        if (lane == 0) { a.pk_val[blockIdx.x * MAXM + r] = v; a.pk_idx[blockIdx.x * MAXM + r] = i; }
       }
     }
   }
@@ -298,18 +428,22 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs a) {
 // cached prefix (the sub-processes all extend x_<=t by one candidate); each
 // row has its own key/value for position p, which this kernel also rotates
 // (RoPE), rounds to the cache type and stores: at cache slot p for the main
-// token, in the row's tail slot for a candidate.
+// token, in the row's tail slot for a candidate.  A workgroup takes one head
+// and one chunk of 128 positions; all its cached keys and values are
+// requested before anything else is done.
 struct AttnGroup {
   const float* qkv;     // [M][3*d_model]: q | k | v as produced by the QKV projection
   const void* Kc; const void* Vc;   // this layer's cache, [H][max_ctx][hd]
-  void* ownK; void* ownV;           // destination of the rows' own key/value
-  long own_row_stride, own_head_stride;   // in elements: dst = own + m*row + h*head + i
+  void* ownK; void* ownV;           // destination of the rows' own key/value: the layer's cache (own_cache) or its tails
+  long own_row_stride, own_head_stride;   // in elements: dst = own + m*row + h*head + i  (+ p*hd when own_cache)
   float* part;          // [M][H][nchunk_max][hd+2] partial (unnormalised o, max, sum)
-  int p;                // number of cached positions attended to = position of the rows
+  int pos_off;          // the rows sit at position p = ds->pos + pos_off and attend to cached positions [0, p)
+  int own_cache;
   int M;
 };
 struct AttnArgs {
   AttnGroup g[2];
+  const DevState* ds;
   const float2* rope;   // [max_ctx][hd/2] (cos, sin) or null
   int H, d_model, max_ctx, nchunk_max;
   float scale;
@@ -321,13 +455,32 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const AttnGroup& G,
   constexpr int LPR = HD / VEC;        // lanes per cached row
   constexpr int RPW = WAVE / LPR;      // cached rows per wave per load
   constexpr int RPP = RPW * ATT_WAVES; // rows per pass of the workgroup
+  constexpr int NP = ATT_CHUNK / RPP;  // passes per chunk
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int h = blockIdx.y, c = blockIdx.x;
-  const int p = G.p, M = G.M;
+  const int p = a.ds->pos + G.pos_off, M = G.M;
   const int j0 = c * ATT_CHUNK;
   if (j0 > p) return;
   const int j1 = (j0 + ATT_CHUNK < p + 1) ? j0 + ATT_CHUNK : p + 1;   // exclusive; position p is the row's own
   const bool owns_p = (p < j0 + ATT_CHUNK);
+  const int cs = lane % LPR, rs = lane / LPR;
+
+  // request the chunk's cached keys and values
+  const char* Kh = (const char*)G.Kc + (size_t)h * a.max_ctx * HD * sizeof(WT);
+  const char* Vh = (const char*)G.Vc + (size_t)h * a.max_ctx * HD * sizeof(WT);
+  u32x4 kreg[NP], vreg[NP];
+#pragma unroll
+  for (int t = 0; t < NP; ++t) {
+    int j = j0 + t * RPP + wave * RPW + rs;
+    if (j < p) {
+      kreg[t] = ld_stream(Kh + ((size_t)j * HD + cs * VEC) * sizeof(WT));
+      vreg[t] = ld_stream(Vh + ((size_t)j * HD + cs * VEC) * sizeof(WT));
+    } else {
+      kreg[t] = (u32x4){0u, 0u, 0u, 0u};
+      vreg[t] = (u32x4){0u, 0u, 0u, 0u};
+    }
+  }
+
   float* qs = lds;                    // [MT][HD]
   float* ko = qs + MT * HD;           // [MT][HD] own key, rounded to cache type
   float* vo = ko + MT * HD;           // [MT][HD]
@@ -343,51 +496,42 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const AttnGroup& G,
     if (a.rope) {
       constexpr int half = HD / 2;
       int ii = i < half ? i : i - half;
-      float2 cs = a.rope[(size_t)p * half + ii];
+      float2 cz = a.rope[(size_t)p * half + ii];
       float qo = i < half ? row[i + half] : row[i - half];
       float kk = i < half ? row[a.d_model + i + half] : row[a.d_model + i - half];
-      if (i < half) { q = fmaf(q, cs.x, -(qo * cs.y)); k = fmaf(k, cs.x, -(kk * cs.y)); }
-      else          { q = fmaf(q, cs.x, qo * cs.y);    k = fmaf(k, cs.x, kk * cs.y); }
+      if (i < half) { q = fmaf(q, cz.x, -(qo * cz.y)); k = fmaf(k, cz.x, -(kk * cz.y)); }
+      else          { q = fmaf(q, cz.x, qo * cz.y);    k = fmaf(k, cz.x, kk * cz.y); }
     }
     qs[m * HD + i] = q * a.scale;
     ko[m * HD + i] = WTr<WT>::round(k);
     vo[m * HD + i] = WTr<WT>::round(v);
     if (owns_p) {
-      size_t d = (size_t)m * G.own_row_stride + (size_t)h * G.own_head_stride + i;
+      size_t d = (size_t)m * G.own_row_stride + (size_t)h * G.own_head_stride + i + (G.own_cache ? (size_t)p * HD : 0);
       WTr<WT>::store1(G.ownK, d, k);
       WTr<WT>::store1(G.ownV, d, v);
     }
   }
   __syncthreads();
 
-  const int cs = lane % LPR, rs = lane / LPR;
   float qr[MT][VEC];
 #pragma unroll
   for (int m = 0; m < MT; ++m)
 #pragma unroll
     for (int e = 0; e < VEC; ++e) qr[m][e] = (m < M) ? qs[m * HD + cs * VEC + e] : 0.f;
 
-  const char* Kh = (const char*)G.Kc + (size_t)h * a.max_ctx * HD * sizeof(WT);
-  const char* Vh = (const char*)G.Vc + (size_t)h * a.max_ctx * HD * sizeof(WT);
-
   // scores
-  for (int base = j0; base < j1; base += RPP) {
-    int j = base + wave * RPW + rs;
+#pragma unroll
+  for (int t = 0; t < NP; ++t) {
+    int j = j0 + t * RPP + wave * RPW + rs;
     bool valid = j < j1;
     float kf[VEC];
-    if (valid && j < p) {
-      uint4 r = *(const uint4*)(Kh + ((size_t)j * HD + cs * VEC) * sizeof(WT));
-      WTr<WT>::unpack(r, kf);
-    } else {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) kf[e] = 0.f;
-    }
+    WTr<WT>::unpack(kreg[t], kf);
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       float s = 0.f;
       if (valid && j == p) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) s = fmaf(qr[m][e], ko[m * HD + cs * VEC + e], s);
+        for (int e = 0; e < VEC; ++e) s = fmaf(qr[m][e], ko[(m < M ? m : 0) * HD + cs * VEC + e], s);
       } else {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) s = fmaf(qr[m][e], kf[e], s);
@@ -420,17 +564,12 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const AttnGroup& G,
   for (int m = 0; m < MT; ++m)
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[m][e] = 0.f;
-  for (int base = j0; base < j1; base += RPP) {
-    int j = base + wave * RPW + rs;
+#pragma unroll
+  for (int t = 0; t < NP; ++t) {
+    int j = j0 + t * RPP + wave * RPW + rs;
     bool valid = j < j1;
     float vf[VEC];
-    if (valid && j < p) {
-      uint4 r = *(const uint4*)(Vh + ((size_t)j * HD + cs * VEC) * sizeof(WT));
-      WTr<WT>::unpack(r, vf);
-    } else {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) vf[e] = 0.f;
-    }
+    WTr<WT>::unpack(vreg[t], vf);
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       if (m >= M) continue;
@@ -487,13 +626,14 @@ template <int HD, int MT> constexpr size_t attn_lds_bytes() {
 // merge of the chunk partials, chunks in index order
 struct MergeArgs {
   const float* part[2]; float* out[2];   // out: [M][d_model]
-  int p[2]; int M[2];
+  int pos_off[2]; int M[2];
+  const DevState* ds;
   int H, HD, d_model, nchunk_max;
 };
 __global__ void attn_merge_kernel(MergeArgs a) {
   int g = blockIdx.z, h = blockIdx.y, m = blockIdx.x;
   if (m >= a.M[g]) return;
-  int nc = a.p[g] / ATT_CHUNK + 1;
+  int nc = (a.ds->pos + a.pos_off[g]) / ATT_CHUNK + 1;
   int i = threadIdx.x;
   if (i >= a.HD) return;
   const float* base = a.part[g] + (((size_t)m * a.H + h) * a.nchunk_max) * (a.HD + 2);
@@ -510,33 +650,46 @@ __global__ void attn_merge_kernel(MergeArgs a) {
 }
 
 // ------------------------------------------------------------------ selection
-// Early prediction: top-k of the early logits by (logit descending, id ascending).
-// Final prediction: arg max of the final logits (ties to the lowest id), then
-// verification against the early candidates (Algorithm 2: "if x-hat^(PID) = x_{t+1}").
-// One workgroup of 1024 threads; every thread keeps its own sorted top-k of a
-// strided slice, then k rounds of a workgroup-wide best-of selection.
+// Early prediction: top-k of the early logits by (logit descending, id ascending); the head GEMM
+// leaves every workgroup's own top-k, this kernel merges them and sets up the k candidate rows
+// (Algorithm 2: "select the top-k early predicted tokens", "distribute" -- here: embed them).
+// Final prediction: arg max of the final logits (ties to the lowest id), verification against the
+// early candidates ("if x-hat^(PID) = x_{t+1}"), then adoption: on a match the matching candidate's
+// hidden row becomes the main row and its key/value tails of layers 1..d-dbar become cache position
+// t+1; without a match nothing is copied and the tails are overwritten by the next round.
 struct SelectArgs {
-  const float* logits; int vocab; int k;
-  int mode;            // 0: early top-k -> cand[0..k); 1: final arg max + verify
-  int32_t* cand;       // DEVICE [MAXM]
-  int32_t* result;     // DEVICE: [0] token, [1] match_idx  (mode 1)
-  int32_t* next_tok;   // DEVICE: token id the next main row embeds (mode 1)
+  const float* pk_val; const int32_t* pk_idx;   // [nblk][MAXM] block candidates, first kk of each valid
+  int nblk; int kk;     // kk = k (early) or 1 (final)
+  int k;
+  int mode;             // 0: early top-k -> cand[0..k) + embed; 1: final arg max + verify + adopt
+  DevState* ds;
+  int32_t* host_result; // device-visible pinned host memory: [0] token, [1] match_idx (mode 1)
+  EmbedArgs emb;        // candidate rows (mode 0)
+  // adoption (mode 1)
+  float* h;                 // [1+k][d_model]: row 0 main, rows 1.. candidates
+  const void* tailK; const void* tailV;   // [nb][k][H][hd]
+  void* Kc; void* Vc;       // [L][H][max_ctx][hd]
+  int nb, H, hd, d_model, max_ctx, wbytes;
 };
-constexpr int SEL_THREADS = 1024;
+constexpr int SEL_THREADS = 256;
 
-__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
-
+// every workgroup merges the block candidates redundantly (they are few); winners land in win[]
+template <typename WT>
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   __shared__ float wv[SEL_THREADS / WAVE];
   __shared__ int wi[SEL_THREADS / WAVE];
-  __shared__ int win_id;
+  __shared__ int win[MAXM];
+  __shared__ int s_midx;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int k = a.mode == 0 ? a.k : 1;
+  const int nk = a.mode == 0 ? a.k : 1;
+  const int total = a.nblk * a.kk;
+  // each thread scans its strided share and keeps its own sorted best nk
   float lv[MAXM]; int li[MAXM];
 #pragma unroll
   for (int q = 0; q < MAXM; ++q) { lv[q] = -INFINITY; li[q] = 0x7fffffff; }
-  for (int i = tid; i < a.vocab; i += SEL_THREADS) {
-    float v = a.logits[i];
+  for (int e = tid; e < total; e += SEL_THREADS) {
+    int b = e / a.kk, r = e - b * a.kk;
+    float v = a.pk_val[b * MAXM + r]; int i = a.pk_idx[b * MAXM + r];
     if (better(v, i, lv[MAXM - 1], li[MAXM - 1])) {
       lv[MAXM - 1] = v; li[MAXM - 1] = i;
 #pragma unroll
@@ -547,66 +700,67 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
         }
     }
   }
-  int head = 0;   // index of this thread's best remaining candidate
-  for (int r = 0; r < k; ++r) {
+  int head = 0;
+  for (int r = 0; r < nk; ++r) {
     float v = -INFINITY; int i = 0x7fffffff;
 #pragma unroll
     for (int q = 0; q < MAXM; ++q) if (q == head) { v = lv[q]; i = li[q]; }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      float ov = __shfl_xor(v, o, WAVE); int oi = __shfl_xor(i, o, WAVE);
-      if (better(ov, oi, v, i)) { v = ov; i = oi; }
-    }
+    wave_best(v, i);
     __syncthreads();
     if (lane == 0) { wv[wave] = v; wi[wave] = i; }
     __syncthreads();
-    if (tid == 0) {
-      int bw = 0;
-      for (int w = 1; w < SEL_THREADS / WAVE; ++w) if (better(wv[w], wi[w], wv[bw], wi[bw])) bw = w;
-      int id = wi[bw];
-      win_id = id;
-      if (a.mode == 0) a.cand[r] = id;
-      else {
-        int midx = -1;
-        for (int q = 0; q < a.k; ++q) if (a.cand[q] == id) { midx = q; break; }
-        a.result[0] = id; a.result[1] = midx; *a.next_tok = id;
-      }
-    }
-    __syncthreads();
-    // ids are unique across threads: only the owner of the winner moves on
-    int wid = win_id;
+    int bw = 0;
+#pragma unroll
+    for (int w = 1; w < SEL_THREADS / WAVE; ++w) if (better(wv[w], wi[w], wv[bw], wi[bw])) bw = w;
+    const int wid = wi[bw];
+    if (tid == 0) win[r] = wid;
     int cur = 0x7fffffff;
 #pragma unroll
     for (int q = 0; q < MAXM; ++q) if (q == head) cur = li[q];
-    if (cur == wid) ++head;
+    if (cur == wid) ++head;     // ids are unique: only the owner of the winner moves on
   }
-}
-
-// ------------------------------------------------------------------ adoption
-// On a match the matching sub-process's state becomes the main process's
-// (Algorithm 2: h^(0)_{d-dbar} <- h^(PID)_{d-dbar}); its key/value tails of layers
-// 1..d-dbar become cache position t+1.  Without a match nothing is copied: the
-// tails are simply overwritten by the next round.
-struct CommitArgs {
-  const int32_t* result;    // DEVICE: [1] = match_idx
-  float* h;                 // [1+k][d_model]: row 0 main, rows 1.. candidates
-  const void* tailK; const void* tailV;   // [nb][k][H][hd]
-  void* Kc; void* Vc;       // [L][H][max_ctx][hd]
-  int k, H, hd, d_model, max_ctx, pos_next, wbytes;
-};
-__global__ void commit_kernel(CommitArgs a) {
-  int midx = a.result[1];
-  if (midx < 0) return;
-  int l = blockIdx.x;
+  __syncthreads();
+  if (a.mode == 0) {
+    // candidates and their rows; block x handles row blockIdx.y
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid < a.k) a.ds->cand[tid] = win[tid];
+    const int r = blockIdx.y;
+    EmbedArgs e = a.emb;
+    int tok = win[r];
+    int pos = a.ds->pos + e.pos_off;
+    for (int i = blockIdx.x * SEL_THREADS + tid; i < e.d_model; i += gridDim.x * SEL_THREADS) {
+      float v = WTr<WT>::load1(e.tok_emb, (size_t)tok * e.d_model + i);
+      if (e.pos_emb) v += WTr<WT>::load1(e.pos_emb, (size_t)pos * e.d_model + i);
+      e.h[(size_t)r * e.d_model + i] = v;
+    }
+    return;
+  }
+  // final: verification
+  const int token = win[0];
+  if (tid == 0) {
+    int midx = -1;
+    for (int q = 0; q < a.k; ++q) if (a.ds->cand[q] == token) { midx = q; break; }
+    s_midx = midx;
+  }
+  __syncthreads();
+  const int midx = s_midx;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) {
+    a.ds->result[0] = token; a.ds->result[1] = midx; a.ds->next_tok = token;
+    a.host_result[0] = token; a.host_result[1] = midx;
+  }
+  if (midx < 0 || a.nb == 0) return;
+  // adoption: block (l, which) copies one layer's K or V tail; block (0,0) also the hidden row
+  const int l = blockIdx.x;
+  if (l >= a.nb) return;
+  const int pos_next = a.ds->pos + 1;
   if (l == 0 && blockIdx.y == 0)
-    for (int i = threadIdx.x; i < a.d_model; i += blockDim.x) a.h[i] = a.h[(size_t)(1 + midx) * a.d_model + i];
+    for (int i = tid; i < a.d_model; i += SEL_THREADS) a.h[i] = a.h[(size_t)(1 + midx) * a.d_model + i];
   const char* src = (const char*)(blockIdx.y == 0 ? a.tailK : a.tailV) + ((size_t)l * a.k + midx) * a.d_model * a.wbytes;
   char* dst = (char*)(blockIdx.y == 0 ? a.Kc : a.Vc) + (size_t)l * a.H * a.max_ctx * a.hd * a.wbytes;
-  int row_bytes = a.hd * a.wbytes;   // multiple of 16
-  for (int idx = threadIdx.x; idx < a.H * (row_bytes / 16); idx += blockDim.x) {
+  const int row_bytes = a.hd * a.wbytes;   // multiple of 16
+  for (int idx = tid; idx < a.H * (row_bytes / 16); idx += SEL_THREADS) {
     int hh = idx / (row_bytes / 16), q = idx - hh * (row_bytes / 16);
     uint4 v = *(const uint4*)(src + (size_t)hh * row_bytes + q * 16);
-    *(uint4*)(dst + ((size_t)hh * a.max_ctx + a.pos_next) * row_bytes + q * 16) = v;
+    *(uint4*)(dst + ((size_t)hh * a.max_ctx + pos_next) * row_bytes + q * 16) = v;
   }
 }
 

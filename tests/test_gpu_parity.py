@@ -79,6 +79,27 @@ def test_ppd_gpu_is_plain_gpu_bit_exact(setup, k):
         P.close()
 
 
+def test_graph_replay_equals_eager_launches(setup):
+    """Rounds replayed from captured HIP graphs give the bits of eagerly issued launches, on every
+    replay (the program's own copies and synchronisations run between replays)."""
+    cfg, m, dev, o = setup
+    prompt = pi.make_prompt(cfg)
+    ell = min(cfg.n_gen, 16)
+    res = []
+    for graphs in (True, False):
+        P = binding.PPD(cfg, dev, k=3)
+        P.ppd_set_graphs(graphs)
+        toks, z, infos = gpu_generate(P, prompt, ell, "ppd")
+        ptoks, pz, _ = gpu_generate(P, prompt, ell, "plain")
+        res.append((toks, z, infos, ptoks, pz))
+        P.close()
+    np.testing.assert_array_equal(res[0][0], res[1][0])
+    np.testing.assert_array_equal(res[0][1], res[1][1])
+    assert res[0][2] == res[1][2]
+    np.testing.assert_array_equal(res[0][3], res[1][3])
+    np.testing.assert_array_equal(res[0][4], res[1][4])
+
+
 def test_mixing_plain_and_ppd_steps(setup):
     cfg, m, dev, o = setup
     prompt = pi.make_prompt(cfg)
