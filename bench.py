@@ -85,14 +85,16 @@ def main():
     wall_plain, _ = timed(P, P.plain_greedy_step, W, K)
 
     # ---- per-kernel timing (HIP events on the library's stream), separate short pass
-    P.ppd_prefill(prompt)
-    for _ in range(W):
-        P.ppd_step(want_info=False)
-    P.ppd_set_profiling(True)
-    for _ in range(args.profile_rounds):
-        P.ppd_step(want_info=False)
-    kt = P.ppd_get_kernel_time()
-    P.ppd_set_profiling(False)
+    kt = {}
+    if args.profile_rounds > 0:
+        P.ppd_prefill(prompt)
+        for _ in range(W):
+            P.ppd_step(want_info=False)
+        P.ppd_set_profiling(True)
+        for _ in range(args.profile_rounds):
+            P.ppd_step(want_info=False)
+        kt = P.ppd_get_kernel_time()
+        P.ppd_set_profiling(False)
     ctx_mid = n_prompt + W + args.profile_rounds // 2
     wl = cfg.layer_weight_bytes()
     ffn_in_bytes = (3 if cfg.act == pi.ACT_SWIGLU else 2) - 1

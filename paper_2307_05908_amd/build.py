@@ -1,17 +1,24 @@
-"""Build libppd.so for gfx950 with hipcc (cross-compiles without a GPU)."""
+"""Build libppd.so for gfx950 with hipcc (cross-compiles without a GPU).
+
+The kernel template instances are spread over several translation units (csrc/ppd_inst.hip with
+-DPPD_INST=n) that compile in parallel; objects go to a scratch directory outside the tree.
+"""
 from __future__ import annotations
 
+import concurrent.futures
 import os
 import subprocess
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libppd.so")
-SOURCES = [os.path.join(HERE, "csrc", "ppd_engine.hip")]
-DEPS = SOURCES + [os.path.join(HERE, "csrc", "ppd_kernels.h"),
-                  os.path.join(os.path.dirname(HERE), "include", "ppd.h")]
+N_INST = 10
+DEPS = [os.path.join(CSRC, f) for f in ("ppd_engine.hip", "ppd_inst.hip", "ppd_kernels.h", "ppd_launch.h")] + \
+       [os.path.join(os.path.dirname(HERE), "include", "ppd.h")]
 # -ffp-contract=off: every fused multiply-add in the kernels is an explicit fmaf, so a row's arithmetic
 # does not depend on which template instance it runs in.  Packed-fp32 code generation is switched off.
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp-contract=off",
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-variable"]
 
 
@@ -19,9 +26,31 @@ def stale() -> bool:
     return (not os.path.exists(LIB_PATH)) or any(os.path.getmtime(LIB_PATH) < os.path.getmtime(s) for s in DEPS)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    if force or stale():
-        cmd = ["hipcc"] + FLAGS + ["-o", LIB_PATH] + SOURCES
+def _compile(args):
+    src, obj, extra, verbose = args
+    cmd = ["hipcc"] + FLAGS + extra + ["-c", src, "-o", obj]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in r.stdout.splitlines() if "is not a recognized feature" not in l)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {src} {extra}:\n{out}")
+    return out
+
+
+def build(force: bool = True, verbose: bool = False, jobs: int = 0) -> str:
+    if not (force or stale()):
+        return LIB_PATH
+    jobs = jobs or min(8, os.cpu_count() or 4)
+    with tempfile.TemporaryDirectory(prefix="ppd_build_") as tmp:
+        units = [(os.path.join(CSRC, "ppd_engine.hip"), os.path.join(tmp, "engine.o"), [], verbose)]
+        for i in range(N_INST):
+            units.append((os.path.join(CSRC, "ppd_inst.hip"), os.path.join(tmp, f"inst{i}.o"), [f"-DPPD_INST={i}"], verbose))
+        with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:
+            for out in ex.map(_compile, units):
+                if out.strip() and verbose:
+                    print(out)
+        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + [u[1] for u in units]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

@@ -1,8 +1,10 @@
 // Host side of libppd: context, round state machine of Algorithm 2, launch
 // sequences.  All arithmetic of the method runs in the kernels of
 // ppd_kernels.h; this file only decides which layers run on which rows.
+#define PPD_ENGINE_TU 1
 #include "../../include/ppd.h"
 #include "ppd_kernels.h"
+#include "ppd_launch.h"
 
 #include <math.h>
 #include <stdlib.h>
@@ -26,7 +28,10 @@ struct ppd_ctx {
   int k, dbar, nb;   // nb = d - dbar: layers each candidate runs, = pipelined steps per round
   hipStream_t user_stream;   // the caller's stream: work of a call is ordered after what it holds
   hipStream_t stream;        // the context's own stream: every launch goes here (a graph cannot be captured on the null stream)
-  hipEvent_t join_ev;
+  hipStream_t stream2;       // second stream: the candidates' layers of the parallel phase run here, next to the main token's
+  hipStream_t cur;           // stream the launch helpers issue to
+  hipEvent_t join_ev, fork_ev, back_ev;
+  int dual;                  // parallel phase as two concurrent chains (1) or as two-group launches (0)
   int wbytes;
   // weights (borrowed)
   const void *tok_emb, *pos_emb, *lnf_g, *lnf_b, *lm_head, *early_head;
@@ -51,7 +56,8 @@ struct ppd_ctx {
   int use_graphs;
   hipGraphExec_t graph[3];
   int graph_chunks[3];   // attention grid (128-position chunks) each graph was captured with
-  int gmax1, gmax2;      // workgroup budget of a GEMM launch: one group / per group of a two-group launch
+  int gmax1, gmax2, gmaxd; // workgroup budget of a GEMM launch: one group / per group of a two-group launch / per chain of the parallel phase
+  int in_dual;           // launches belong to one of two concurrent chains
   int nchunk_max;
   // round state
   int n_ctx;      // absolute position of the pending token x_t (-1: no prefill yet)
@@ -85,7 +91,7 @@ int g_create_hip_error = 0;   // hipError_t of the last ppd_create that failed w
 inline size_t cache_layer_bytes(const ppd_ctx* c) { return (size_t)c->d.max_ctx * c->d.d_model * c->wbytes; }
 
 struct ProfScope {
-  ppd_ctx* c; int cls; size_t idx; bool on;
+  ppd_ctx* c; int cls; size_t idx; bool on; hipStream_t st = nullptr;
   ProfScope(ppd_ctx* c_, int cls_, int groups = 1) : c(c_), cls(cls_ + (groups - 1) * PPD_KC_COUNT), idx(0), on(c_->prof != 0) {
     if (!on) return;
     if (c->ev_used + 2 > c->ev.size()) {
@@ -94,9 +100,9 @@ struct ProfScope {
     }
     idx = c->ev_used; c->ev_used += 2;
     c->ev_class[idx / 2] = cls;
-    (void)hipEventRecord(c->ev[idx], c->stream);
+    st = c->cur; (void)hipEventRecord(c->ev[idx], st);
   }
-  ~ProfScope() { if (on) (void)hipEventRecord(c->ev[idx + 1], c->stream); }
+  ~ProfScope() { if (on) (void)hipEventRecord(c->ev[idx + 1], st); }
 };
 
 void prof_collect(ppd_ctx* c) {   // stream must be idle
@@ -111,20 +117,6 @@ void prof_collect(ppd_ctx* c) {   // stream must be idle
 }
 
 // ------------------------------------------------------------ launch helpers
-constexpr int max1(int x) { return x < 1 ? 1 : x; }
-template <typename WT, bool PAIRED>
-hipError_t launch_gemm_t(ppd_ctx* c, const GemmArgs& a, int ngroups, int MB, dim3 grid, size_t lds) {
-#define GO(mb) hipLaunchKernelGGL((gemm_kernel<WT, 1, mb, PAIRED>), grid, dim3(GEMM_THREADS), lds, c->stream, a)
-  if (ngroups == 1) { GO(0); return hipGetLastError(); }
-  switch (MB) {
-    case 1: GO(1); break; case 2: GO(2); break; case 3: GO(3); break; case 4: GO(4); break;
-    case 5: GO(5); break; case 6: GO(6); break; case 7: GO(7); break; case 8: GO(8); break;
-    default: return hipErrorInvalidValue;
-  }
-#undef GO
-  return hipGetLastError();
-}
-
 // Workgroups per group for a GEMM with `nsets` row sets: each workgroup has four waves and every
 // wave takes ceil(nsets / waves) sets, so pick the count in [gmax/2, gmax] that wastes the fewest
 // wave slots (ties: the larger grid).
@@ -143,41 +135,38 @@ int pick_grid(int nsets, int gmax) {
 // one skinny GEMM launch; group 0 is always one row, group 1 (optional) has MB rows
 hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
   const int vec = 16 / c->wbytes;
-  const int span = GEMM_NB * WAVE * vec;
-  const int mmax = ngroups == 2 ? (a.g[1].M > 1 ? a.g[1].M : 1) : 1;
-  int kc_cap = (int)((60 * 1024) / (mmax * sizeof(float))) / span * span;
-  if (kc_cap < span) kc_cap = span;
-  const int kpad = (a.K + span - 1) / span * span;
+  const int gmax = ngroups == 2 ? c->gmax2 : (c->in_dual ? c->gmaxd : c->gmax1);
+  const int mmax = ngroups == 2 ? (a.g[1].M > a.g[0].M ? a.g[1].M : a.g[0].M) : a.g[0].M;
+  const int x_budget = GEMM_X_FLOATS / mmax;   // k elements of x per row that fit the LDS tile
+  // rows a wave streams together: 4, or 2 when 4 would leave waves of the grid without a set
+  int wr = 4;
+  const int wrows = a.ntot * (paired ? 2 : 1);
+  if (a.topk == 0 && (wrows + 3) / 4 < gmax * GEMM_WAVES && x_budget >= (GEMM_BATCH / 2) * WAVE * vec && x_budget >= GEMM_THREADS * 4) wr = 2;
+  int span2 = (GEMM_BATCH / wr) * WAVE * vec;
+  if (span2 < GEMM_THREADS * 4) span2 = GEMM_THREADS * 4;   // tile rows are a whole number of float4 per thread too
+  int kc_cap = x_budget / span2 * span2;
+  if (kc_cap < span2) kc_cap = span2;
+  const int kpad = (a.K + span2 - 1) / span2 * span2;
   a.KC = kpad < kc_cap ? kpad : kc_cap;
-  const int lr = paired ? GEMM_WROWS / 2 : GEMM_WROWS;
+  const int lr = paired ? wr / 2 : wr;
   const int nsets = (a.ntot + lr - 1) / lr;
   int gx;
   if (a.topk > 0) gx = c->head_grid;
-  else gx = pick_grid(nsets, ngroups == 2 ? c->gmax2 : c->gmax1);
+  else gx = pick_grid(nsets, gmax);
   dim3 grid(gx, ngroups);
   size_t lds = (GEMM_LDS_HDR + (size_t)mmax * a.KC + (a.topk > 0 ? HEAD_MAX_ROWS : 0)) * sizeof(float);
   int MB = ngroups == 2 ? a.g[1].M : 0;
-  if (c->wbytes == 4) return paired ? launch_gemm_t<float, true>(c, a, ngroups, MB, grid, lds)
-                                    : launch_gemm_t<float, false>(c, a, ngroups, MB, grid, lds);
-  return paired ? launch_gemm_t<bf16_t, true>(c, a, ngroups, MB, grid, lds)
-                : launch_gemm_t<bf16_t, false>(c, a, ngroups, MB, grid, lds);
-}
-
-template <typename WT, int HD>
-hipError_t launch_attn_t(ppd_ctx* c, const AttnArgs& a, int ngroups, int MB, dim3 grid) {
-#define GO(mb)                                                              \
-  do {                                                                      \
-    constexpr size_t lds_ = attn_lds_bytes<HD, max1(mb)>();                 \
-    attn_kernel<WT, HD, 1, mb><<<grid, dim3(ATT_THREADS), lds_, c->stream>>>(a); \
-  } while (0)
-  if (ngroups == 1) { GO(0); return hipGetLastError(); }
-  switch (MB) {
-    case 1: GO(1); break; case 2: GO(2); break; case 3: GO(3); break; case 4: GO(4); break;
-    case 5: GO(5); break; case 6: GO(6); break; case 7: GO(7); break; case 8: GO(8); break;
-    default: return hipErrorInvalidValue;
+  const int MA = a.g[0].M;
+  if (c->wbytes == 4) {
+    if (wr == 4) return paired ? launch_gemm_t<float, true, 4>(c->cur, a, MA, MB, grid, lds)
+                               : launch_gemm_t<float, false, 4>(c->cur, a, MA, MB, grid, lds);
+    return paired ? launch_gemm_t<float, true, 2>(c->cur, a, MA, MB, grid, lds)
+                  : launch_gemm_t<float, false, 2>(c->cur, a, MA, MB, grid, lds);
   }
-#undef GO
-  return hipGetLastError();
+  if (wr == 4) return paired ? launch_gemm_t<bf16_t, true, 4>(c->cur, a, MA, MB, grid, lds)
+                             : launch_gemm_t<bf16_t, false, 4>(c->cur, a, MA, MB, grid, lds);
+  return paired ? launch_gemm_t<bf16_t, true, 2>(c->cur, a, MA, MB, grid, lds)
+                : launch_gemm_t<bf16_t, false, 2>(c->cur, a, MA, MB, grid, lds);
 }
 
 // pmax: largest position any row of the launch sits at (host-side bound for the grid; the kernel
@@ -185,12 +174,13 @@ hipError_t launch_attn_t(ppd_ctx* c, const AttnArgs& a, int ngroups, int MB, dim
 hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups, int pmax) {
   dim3 grid(pmax / ATT_CHUNK + 1, a.H, ngroups);
   int MB = ngroups == 2 ? a.g[1].M : 0;
+  const int MA = a.g[0].M;
   if (c->wbytes == 4) {
-    if (c->d.head_dim == 64) return launch_attn_t<float, 64>(c, a, ngroups, MB, grid);
-    return launch_attn_t<float, 128>(c, a, ngroups, MB, grid);
+    if (c->d.head_dim == 64) return launch_attn_t<float, 64>(c->cur, a, MA, MB, grid);
+    return launch_attn_t<float, 128>(c->cur, a, MA, MB, grid);
   }
-  if (c->d.head_dim == 64) return launch_attn_t<bf16_t, 64>(c, a, ngroups, MB, grid);
-  return launch_attn_t<bf16_t, 128>(c, a, ngroups, MB, grid);
+  if (c->d.head_dim == 64) return launch_attn_t<bf16_t, 64>(c->cur, a, MA, MB, grid);
+  return launch_attn_t<bf16_t, 128>(c->cur, a, MA, MB, grid);
 }
 
 // A row group of one layer step: which layer, how many rows, first row in the
@@ -257,7 +247,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     mg.H = d.n_heads; mg.HD = d.head_dim; mg.d_model = dm; mg.nchunk_max = c->nchunk_max;
     int mmax = rg[0].M; if (ngroups == 2 && rg[1].M > mmax) mmax = rg[1].M;
     ProfScope ps(c, PPD_KC_ATTN_MERGE, ngroups);
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(mmax, d.n_heads, ngroups), dim3(d.head_dim), 0, c->stream, mg);
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(mmax, d.n_heads, ngroups), dim3(d.head_dim), 0, c->cur, mg);
     HIPCHK(c, hipGetLastError());
   }
   // 3. output projection + residual
@@ -317,14 +307,14 @@ int run_embed(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos_of
   EmbedArgs a = embed_args(c, ids_dev, rows, row0, pos_off);
   dim3 grid((c->d.d_model + 255) / 256, rows);
   ProfScope ps(c, PPD_KC_EMBED);
-  if (c->wbytes == 4) hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, c->stream, a);
-  else hipLaunchKernelGGL(embed_kernel<bf16_t>, grid, dim3(256), 0, c->stream, a);
+  if (c->wbytes == 4) hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, c->cur, a);
+  else hipLaunchKernelGGL(embed_kernel<bf16_t>, grid, dim3(256), 0, c->cur, a);
   HIPCHK(c, hipGetLastError());
   return PPD_OK;
 }
 
 int set_state(ppd_ctx* c, int pos, int tok) {
-  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->stream, c->ds, pos, tok);
+  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->cur, c->ds, pos, tok);
   HIPCHK(c, hipGetLastError());
   return PPD_OK;
 }
@@ -359,8 +349,8 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     grid = dim3(c->nb, 2);
   }
   ProfScope ps(c, PPD_KC_SELECT);
-  if (c->wbytes == 4) hipLaunchKernelGGL(select_kernel<float>, grid, dim3(SEL_THREADS), 0, c->stream, s);
-  else hipLaunchKernelGGL(select_kernel<bf16_t>, grid, dim3(SEL_THREADS), 0, c->stream, s);
+  if (c->wbytes == 4) hipLaunchKernelGGL(select_kernel<float>, grid, dim3(SEL_THREADS), 0, c->cur, s);
+  else hipLaunchKernelGGL(select_kernel<bf16_t>, grid, dim3(SEL_THREADS), 0, c->cur, s);
   HIPCHK(c, hipGetLastError());
   return PPD_OK;
 }
@@ -392,7 +382,26 @@ int issue_round(ppd_ctx* c, int kind, int pmax) {
   // early prediction; the candidates become rows 1..k at the next position
   if ((rc = run_head(c, true, false))) return rc;
   // parallel phase: step j runs the main row at layer dbar+j and the candidates at layer j
-  {
+  if (c->dual) {
+    // two concurrent chains, one per stream: while one chain sits in a latency-bound stretch
+    // (kernel boundary, attention, staging of its input rows) the other keeps HBM busy
+    ProfScope phase(c, PPD_KC_PHASE, 2);
+    c->in_dual = 1;
+    HIPCHK(c, hipEventRecord(c->fork_ev, c->stream));
+    HIPCHK(c, hipStreamWaitEvent(c->stream2, c->fork_ev, 0));
+    for (int j = 0; j < nb && !rc; ++j) {
+      RowGroup gm{dbar + j, 1, 0, 0, false}, gb{j, k, 1, 1, true};
+      c->cur = c->stream;
+      rc = run_layer(c, 1, &gm, pmax);
+      c->cur = c->stream2;
+      if (!rc) rc = run_layer(c, 1, &gb, pmax);
+    }
+    c->cur = c->stream;
+    c->in_dual = 0;
+    HIPCHK(c, hipEventRecord(c->back_ev, c->stream2));
+    HIPCHK(c, hipStreamWaitEvent(c->stream, c->back_ev, 0));
+    if (rc) return rc;
+  } else {
     ProfScope phase(c, PPD_KC_PHASE, 2);
     for (int j = 0; j < nb; ++j) {
       RowGroup g[2] = {{dbar + j, 1, 0, 0, false}, {j, k, 1, 1, true}};
@@ -462,6 +471,9 @@ void free_all(ppd_ctx* c) {
   if (c->host_result) (void)hipHostFree(c->host_result);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   if (c->join_ev) (void)hipEventDestroy(c->join_ev);
+  if (c->fork_ev) (void)hipEventDestroy(c->fork_ev);
+  if (c->back_ev) (void)hipEventDestroy(c->back_ev);
+  if (c->stream2) (void)hipStreamDestroy(c->stream2);
   if (c->stream) (void)hipStreamDestroy(c->stream);
 }
 
@@ -521,14 +533,16 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   c->nchunk_max = (d.max_ctx + ATT_CHUNK - 1) / ATT_CHUNK;
   c->n_ctx = -1;
   c->use_graphs = env_int("PPD_GRAPHS", 1) != 2;      // PPD_GRAPHS=2 switches graph replay off
+  c->dual = env_int("PPD_DUAL", 1) != 2;               // PPD_DUAL=2: two-group launches instead of two chains
   c->gmax1 = env_int("PPD_GMAX1", 512);
+  c->gmaxd = env_int("PPD_GMAXD", 256);
   c->gmax2 = env_int("PPD_GMAX2", 256);
   // head GEMM: as many workgroups as a plain GEMM, more if a workgroup would otherwise
   // produce over HEAD_MAX_ROWS logits
   {
-    const int nsets = (d.vocab + GEMM_WROWS - 1) / GEMM_WROWS;
+    const int nsets = (d.vocab + 3) / 4;                          // the head always streams four rows per wave
     int g = pick_grid(nsets, c->gmax1);
-    const int sets_per_wg_cap = HEAD_MAX_ROWS / GEMM_WROWS;      // per workgroup, all four waves together
+    const int sets_per_wg_cap = HEAD_MAX_ROWS / 4;               // per workgroup, all four waves together
     while (((nsets + g * GEMM_WAVES - 1) / (g * GEMM_WAVES)) * GEMM_WAVES > sets_per_wg_cap) ++g;
     c->head_grid = g;
   }
@@ -554,7 +568,11 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, 2 * sizeof(int32_t), hipHostMallocMapped);
   if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&c->host_result_dev, c->host_result, 0);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking);
+  c->cur = c->stream;
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->back_ev, hipEventDisableTiming);
   if (e == hipSuccess && d.pos == 1) {
     // (cos, sin) of pos * theta^(-2i/hd), evaluated in double on the host
     const int half = d.head_dim / 2;

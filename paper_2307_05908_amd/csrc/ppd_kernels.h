@@ -26,9 +26,10 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int WAVE = 64;
 constexpr int GEMM_THREADS = 256;   // 4 waves
 constexpr int GEMM_WAVES = GEMM_THREADS / WAVE;
-constexpr int GEMM_WROWS = 4;       // weight rows a wave streams together
-constexpr int GEMM_NB = 2;          // k-blocks (64 lanes x 16 bytes each) per register batch
-constexpr int GEMM_LDS_HDR = 96;    // floats in front of the x tile: norm statistics and their reduction scratch
+constexpr int GEMM_X_FLOATS = 15360; // floats of the LDS x tile (60 KB): 15 float4 per thread
+constexpr int GEMM_BATCH = 8;       // 16-byte loads per lane in one register batch: WR weight rows x 8/WR k-blocks
+constexpr int GEMM_AHEAD = 3;       // batches requested ahead of the arithmetic (ring of four register buffers)
+constexpr int GEMM_LDS_HDR = 80;    // floats in front of the x tile: norm statistics and their reduction scratch
 constexpr int HEAD_MAX_ROWS = 256;  // logits one workgroup of the head GEMM may produce (block top-k buffer)
 constexpr int ATT_THREADS = 256;
 constexpr int ATT_WAVES = ATT_THREADS / WAVE;
@@ -99,9 +100,12 @@ __device__ __forceinline__ void wave_best(float& v, int& i) {
 }
 
 // ------------------------------------------------------------------ round state
+// (plain, non-template kernels are compiled into the engine's translation unit only)
+#ifdef PPD_ENGINE_TU
 __global__ void set_state_kernel(DevState* ds, int pos, int tok) {
   if (threadIdx.x == 0) { ds->pos = pos; if (tok >= 0) ds->next_tok = tok; }
 }
+#endif
 
 // ------------------------------------------------------------------ embedding
 // Row set-up (start of the main process, start of every sub-process): h_0 = E[token] (+ P[pos]).
@@ -132,10 +136,11 @@ __global__ void embed_kernel(EmbedArgs a) {
 // The layer forward of the main process and of the sub-processes (Algorithm 2);
 // the sub-processes' k rows share one pass over their layer's weights.
 //
-// A workgroup stages its group's (normalised) input rows in LDS once, then its
-// four waves each stream sets of four weight rows with 16-byte non-temporal
-// loads, one register batch ahead of the arithmetic.  The first batch is
-// requested before the input rows are staged.
+// A workgroup requests its group's input rows, then the first three register
+// batches of its weight rows, and only then normalises the rows and puts them
+// in LDS: a wave's loads return in order, so the rows arrive first and the
+// weights stream in behind them.  Its four waves each take sets of weight rows,
+// read with 16-byte non-temporal loads three batches ahead of the arithmetic.
 struct GemmGroup {
   const float* X;     // [M][ldx] input rows (before the fused norm)
   const float* Rsd;   // residual rows [M][ldy] added in the epilogue, or null
@@ -154,7 +159,7 @@ struct GemmArgs {
   int norm;         // -1 none, 0 LayerNorm, 1 RMSNorm
   float eps;
   int act;          // 0 none, 1 GELU, 2 ReLU, 3 SwiGLU (pairs W[0], W[1])
-  int KC;           // K elements staged in LDS at a time (multiple of GEMM_NB*64*VEC)
+  int KC;           // K elements staged in LDS at a time (multiple of the batch span (8/WR)*64*VEC)
   int topk;         // > 0: LM-head launch; every workgroup also writes its own top-k (value, id)
   float* pk_val; int32_t* pk_idx;   // [gridDim.x][MAXM] block candidates (topk > 0)
 };
@@ -162,39 +167,44 @@ struct GemmArgs {
 __device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
 __device__ __forceinline__ float silu(float u) { return u / (1.0f + expf(-u)); }
 
-template <typename WT, int MT, bool PAIRED>
+// WR: weight rows a wave streams together (4, or 2 when the matrix has few rows per wave);
+// a register batch is always 8 loads per lane: WR rows x (8 / WR) k-blocks.
+template <typename WT, int MT, bool PAIRED, int WR>
 __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G, float* lds) {
   constexpr int VEC = WTr<WT>::VEC;
   constexpr int BK = WAVE * VEC;                 // k elements per block
-  constexpr int SPAN = GEMM_NB * BK;             // k elements per batch
-  constexpr int LR = PAIRED ? GEMM_WROWS / 2 : GEMM_WROWS;  // logical rows per set
+  constexpr int NBK = GEMM_BATCH / WR;           // k-blocks per batch
+  constexpr int SPAN = NBK * BK;                 // k elements per batch
+  constexpr int LR = PAIRED ? WR / 2 : WR;       // logical rows per set
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int M = G.M, K = a.K, KC = a.KC;
-  float* stat = lds;                  // mu[MAXM], rstd[MAXM]
-  float* redA = lds + 16;             // [MAXM][GEMM_WAVES] partial sums
-  float* redB = lds + 48;             // [MAXM][GEMM_WAVES] partial sums of squared deviations
   float4* xs4 = (float4*)(lds + GEMM_LDS_HDR);  // [MT][KC/4] float4; for VEC == 8 the two halves of every 8-group are split
 
   const int nsets = (a.ntot + LR - 1) / LR;
   const int nwaves = gridDim.x * GEMM_WAVES;
   const int gw = blockIdx.x * GEMM_WAVES + wave;
-  const int nit = (nsets + nwaves - 1) / nwaves;           // sets per wave, the same count for every wave
   const int nbps = (K + SPAN - 1) / SPAN;                  // batches per set
   const int bpc = KC / SPAN;                               // batches per staged chunk
   const bool single = KC >= K;
+  // Sets gw, gw + nwaves, ... belong to this wave.  When the reduction length is staged in
+  // chunks the waves of a workgroup meet at barriers, so they all run the same number of sets
+  // (a wave without a set left repeats its last one and drops the result).
+  const int nmine = gw < nsets ? (nsets - gw + nwaves - 1) / nwaves : 0;
+  const int nit = single ? nmine : (nsets + nwaves - 1) / nwaves;
   const int Q = nit * nbps;
 
-  // ---- load side: one batch ahead
-  const char* wp[GEMM_WROWS];
-  bool lvalid = false;
+  // ---- load side: runs GEMM_AHEAD batches ahead of the arithmetic.  Every request is issued
+  // unconditionally (lanes past the end of a row re-read its last 16 bytes and zero them), so
+  // the loads of one wave return in a known order and the arithmetic waits for its own batch only.
+  const char* wp[WR];
+  int l_it = 0, l_b = 0;
   auto set_rows = [&](int it) {
     int s = gw + it * nwaves;
-    lvalid = s < nsets;
+    if (s >= nsets) s = nsets - 1;
 #pragma unroll
     for (int r = 0; r < LR; ++r) {
       int n = s * LR + r;
       int nc = n < a.ntot ? n : a.ntot - 1;
-      if (nc < 0) nc = 0;
       if (PAIRED) {
         wp[2 * r] = (const char*)G.W[0] + (size_t)nc * K * sizeof(WT);
         wp[2 * r + 1] = (const char*)G.W[1] + (size_t)nc * K * sizeof(WT);
@@ -205,25 +215,148 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G,
       }
     }
   };
-  auto issue = [&](int b, u32x4 (&buf)[GEMM_NB][GEMM_WROWS]) {
+  // request batch (l_it, l_b) into buf and move on.  Once the wave has requested all its batches
+  // the loads go to the start of the (cache-resident) input row instead: still issued, never used.
+  const char* idle = (const char*)(G.X + (lane * 4) % K);
+  bool l_done = false;
+  auto issue_next = [&](u32x4 (&buf)[NBK][WR]) {
 #pragma unroll
-    for (int j = 0; j < GEMM_NB; ++j) {
-      int k = b * SPAN + j * BK + lane * VEC;
-      bool ok = lvalid && k < K;
+    for (int j = 0; j < NBK; ++j) {
+      const int k = l_b * SPAN + j * BK + lane * VEC;
+      const int kcl = k < K ? k : K - VEC;
 #pragma unroll
-      for (int r = 0; r < GEMM_WROWS; ++r) {
-        if (ok) buf[j][r] = ld_stream(wp[r] + (size_t)k * sizeof(WT));
-        else buf[j][r] = (u32x4){0u, 0u, 0u, 0u};
-      }
+      for (int r = 0; r < WR; ++r) buf[j][r] = ld_stream(l_done ? idle : wp[r] + (size_t)kcl * sizeof(WT));
+    }
+    if (l_b + 1 < nbps) ++l_b;
+    else if (l_it + 1 < nit) { l_b = 0; ++l_it; set_rows(l_it); }
+    else l_done = true;
+  };
+  // zero what lies past the end of the row
+  auto mask_tail = [&](int c_b, u32x4 (&buf)[NBK][WR]) {
+#pragma unroll
+    for (int j = 0; j < NBK; ++j) {
+      const bool ok = c_b * SPAN + j * BK + lane * VEC < K;
+#pragma unroll
+      for (int r = 0; r < WR; ++r)
+        if (!ok) buf[j][r] = (u32x4){0u, 0u, 0u, 0u};
     }
   };
 
-  u32x4 bufA[GEMM_NB][GEMM_WROWS], bufB[GEMM_NB][GEMM_WROWS];
-  int l_it = 0, l_b = 0;
+  float* stat = lds;                  // mu[MAXM], rstd[MAXM]
+  float* redA = lds + 16;             // [MAXM][GEMM_WAVES] partial sums
+  float* redB = lds + 48;             // [MAXM][GEMM_WAVES] partial sums of squared deviations
+  u32x4 b0[NBK][WR], b1[NBK][WR], b2[NBK][WR], b3[NBK][WR];
   set_rows(0);
-  issue(0, bufA);
 
-  // ---- stage x rows [k0, k0 + KC) into LDS, normalised when the launch fuses a norm
+  // Norm statistics use one fixed order per row whatever the tile shape: thread t owns the
+  // elements k = 4t + 1024 j (+0..3), sums them for j = 0, 1, ... in turn, then a butterfly
+  // inside each wave, then the four wave sums in index order.  LayerNorm: mean first, then
+  // the squared deviations.
+  auto combine4 = [&](const float* r) { return ((r[0] + r[1]) + r[2]) + r[3]; };
+  constexpr int XR = GEMM_X_FLOATS / (GEMM_THREADS * 4);   // float4 registers per thread that hold the whole tile
+  if (single) {
+    // The whole reduction length fits the tile.  Memory returns a wave's loads in order, so the
+    // input rows (and gains) are requested first, the weight batches right behind them, and
+    // everything up to the staged tile then only waits for the rows.
+    const int spr = KC >> 10;              // float4 slots per row per thread
+    float4 xr[XR];
+#pragma unroll
+    for (int i = 0; i < XR; ++i) {
+      xr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      const int m = i / spr, kk = (i - m * spr) * 1024 + tid * 4;
+      if (m < M && kk < K) xr[i] = *(const float4*)(G.X + (size_t)m * a.ldx + kk);
+    }
+    issue_next(b0);
+    issue_next(b1);
+    issue_next(b2);
+    if (a.norm >= 0) {
+      if (a.norm == 0) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+          float sm = 0.f;
+#pragma unroll
+          for (int i = 0; i < XR; ++i)
+            if (i / spr == m) { sm += xr[i].x; sm += xr[i].y; sm += xr[i].z; sm += xr[i].w; }
+          sm = wave_sum(sm);
+          if (lane == 0) redA[m * GEMM_WAVES + wave] = sm;
+        }
+        __syncthreads();
+      }
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        const float mu = a.norm == 0 ? combine4(redA + m * GEMM_WAVES) / (float)K : 0.f;
+        float s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < XR; ++i)
+          if (i / spr == m && (i - m * spr) * 1024 + tid * 4 < K) {
+            float d0 = xr[i].x - mu, d1 = xr[i].y - mu, d2 = xr[i].z - mu, d3 = xr[i].w - mu;
+            s2 = fmaf(d0, d0, s2); s2 = fmaf(d1, d1, s2); s2 = fmaf(d2, d2, s2); s2 = fmaf(d3, d3, s2);
+          }
+        s2 = wave_sum(s2);
+        if (lane == 0) redB[m * GEMM_WAVES + wave] = s2;
+        if (tid == 0) stat[m] = mu;
+      }
+      __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < XR; ++i) {
+      const int m = i / spr, kk = (i - m * spr) * 1024 + tid * 4;
+      if (m >= M) continue;
+      float4 v = xr[i];
+      if (a.norm >= 0 && kk < K) {
+        const float mu = stat[m];
+        const float rs = 1.0f / sqrtf(combine4(redB + m * GEMM_WAVES) / (float)K + a.eps);
+        float xv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float t = (xv[e] - mu) * rs * WTr<WT>::load1(G.ng, kk + e);
+          if (G.nb) t += WTr<WT>::load1(G.nb, kk + e);
+          xv[e] = t;
+        }
+        v = make_float4(xv[0], xv[1], xv[2], xv[3]);
+      }
+      int slot = (VEC == 8) ? (((kk & 7) >> 2) * (KC >> 3) + (kk >> 3)) : (kk >> 2);
+      xs4[m * (KC >> 2) + slot] = v;       // beyond K: zeros (the weights there are zero too)
+    }
+    __syncthreads();
+  } else {
+    // The reduction length is staged chunk by chunk.  Statistics first (same order as above).
+    if (a.norm >= 0) {
+      if (a.norm == 0) {
+        for (int m = 0; m < M; ++m) {
+          const float* x = G.X + (size_t)m * a.ldx;
+          float sm = 0.f;
+          for (int i = tid * 4; i < K; i += 1024) {
+            float4 v = *(const float4*)(x + i);
+            sm += v.x; sm += v.y; sm += v.z; sm += v.w;
+          }
+          sm = wave_sum(sm);
+          if (lane == 0) redA[m * GEMM_WAVES + wave] = sm;
+        }
+        __syncthreads();
+      }
+      for (int m = 0; m < M; ++m) {
+        const float* x = G.X + (size_t)m * a.ldx;
+        const float mu = a.norm == 0 ? combine4(redA + m * GEMM_WAVES) / (float)K : 0.f;
+        float s2 = 0.f;
+        for (int i = tid * 4; i < K; i += 1024) {
+          float4 v = *(const float4*)(x + i);
+          float d0 = v.x - mu, d1 = v.y - mu, d2 = v.z - mu, d3 = v.w - mu;
+          s2 = fmaf(d0, d0, s2); s2 = fmaf(d1, d1, s2); s2 = fmaf(d2, d2, s2); s2 = fmaf(d3, d3, s2);
+        }
+        s2 = wave_sum(s2);
+        if (lane == 0) redB[m * GEMM_WAVES + wave] = s2;
+        if (tid == 0) stat[m] = mu;
+      }
+      __syncthreads();
+      if (tid < M) stat[MAXM + tid] = 1.0f / sqrtf(combine4(redB + tid * GEMM_WAVES) / (float)K + a.eps);
+      // (the barrier in front of the first chunk's staging publishes stat[])
+    }
+    issue_next(b0);
+    issue_next(b1);
+    issue_next(b2);
+  }
+  // chunked mode: x rows [k0, k0 + KC) -> LDS, normalised when the launch fuses a norm
   auto stage = [&](int k0) {
     const int kc = (K - k0) < KC ? (K - k0) : KC;          // valid elements, multiple of VEC (>= 4)
     for (int idx = tid * 4; idx < M * KC; idx += GEMM_THREADS * 4) {
@@ -248,68 +381,45 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G,
     }
   };
 
-  // ---- statistics of the fused norm, per row in one fixed order: every thread sums a strided
-  // share of the row (float4 at 4*tid, 4*tid + 1024, ...), butterfly inside each wave, then the
-  // four wave sums in index order.  LayerNorm: mean first, then the squared deviations.
-  if (a.norm >= 0) {
-    if (a.norm == 0) {
-      for (int m = 0; m < M; ++m) {
-        const float* x = G.X + (size_t)m * a.ldx;
-        float s = 0.f;
-        for (int i = tid * 4; i < K; i += GEMM_THREADS * 4) {
-          float4 v = *(const float4*)(x + i);
-          s += v.x; s += v.y; s += v.z; s += v.w;
-        }
-        s = wave_sum(s);
-        if (lane == 0) redA[m * GEMM_WAVES + wave] = s;
-      }
-      __syncthreads();
-    }
-    for (int m = 0; m < M; ++m) {
-      const float* x = G.X + (size_t)m * a.ldx;
-      float mu = 0.f;
-      if (a.norm == 0) mu = (((redA[m * GEMM_WAVES] + redA[m * GEMM_WAVES + 1]) + redA[m * GEMM_WAVES + 2]) + redA[m * GEMM_WAVES + 3]) / (float)K;
-      float s2 = 0.f;
-      for (int i = tid * 4; i < K; i += GEMM_THREADS * 4) {
-        float4 v = *(const float4*)(x + i);
-        float d0 = v.x - mu, d1 = v.y - mu, d2 = v.z - mu, d3 = v.w - mu;
-        s2 = fmaf(d0, d0, s2); s2 = fmaf(d1, d1, s2); s2 = fmaf(d2, d2, s2); s2 = fmaf(d3, d3, s2);
-      }
-      s2 = wave_sum(s2);
-      if (lane == 0) redB[m * GEMM_WAVES + wave] = s2;
-      if (tid == 0) stat[m] = mu;
-    }
-    __syncthreads();
-    if (tid < M) {
-      float var = (((redB[tid * GEMM_WAVES] + redB[tid * GEMM_WAVES + 1]) + redB[tid * GEMM_WAVES + 2]) + redB[tid * GEMM_WAVES + 3]) / (float)K;
-      stat[MAXM + tid] = 1.0f / sqrtf(var + a.eps);
-    }
-    __syncthreads();
-  }
-  if (single) { stage(0); __syncthreads(); }
-
-  float acc[GEMM_WROWS][MT];
+  float acc[WR][MT];
 #pragma unroll
-  for (int r = 0; r < GEMM_WROWS; ++r)
+  for (int r = 0; r < WR; ++r)
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[r][m] = 0.f;
   float* hlog = lds + GEMM_LDS_HDR + (size_t)MT * KC;   // [HEAD_MAX_ROWS] logits of this workgroup (topk launches)
+  float pb[WR], prs[LR][MT];                            // bias and residual of the current set
 
-  auto step = [&](int q, u32x4 (&cur)[GEMM_NB][GEMM_WROWS], u32x4 (&nxt)[GEMM_NB][GEMM_WROWS]) {
+  // arithmetic of batch q (held in cur)
+  auto step = [&](int q, u32x4 (&cur)[NBK][WR]) {
     const int c_it = q / nbps, c_b = q - c_it * nbps;
-    // request the next batch
-    if (q + 1 < Q) {
-      if (++l_b == nbps) { l_b = 0; ++l_it; set_rows(l_it); }
-      issue(l_b, nxt);
-    }
     if (!single && (c_b % bpc) == 0) {
       __syncthreads();
       stage(c_b * SPAN);
       __syncthreads();
     }
+    if (c_b == nbps - 1) mask_tail(c_b, cur);
+    if (c_b == 0) {
+      // bias and residual of this set's outputs: requested now, needed after the set's last batch
+      const int s0 = gw + c_it * nwaves;
+#pragma unroll
+      for (int r = 0; r < LR; ++r) {
+        int n = s0 * LR + r;
+        if (n >= a.ntot) n = a.ntot - 1;
+        if (PAIRED) {
+          pb[2 * r] = G.B[0] ? WTr<WT>::load1(G.B[0], n) : 0.f;
+          pb[2 * r + 1] = G.B[1] ? WTr<WT>::load1(G.B[1], n) : 0.f;
+        } else {
+          int seg = 0, loc = n;
+          if (loc >= a.N[0]) { loc -= a.N[0]; seg = 1; if (loc >= a.N[1]) { loc -= a.N[1]; seg = 2; } }
+          pb[r] = G.B[seg] ? WTr<WT>::load1(G.B[seg], loc) : 0.f;
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m) prs[r][m] = (G.Rsd && m < M) ? G.Rsd[(size_t)m * a.ldy + n] : 0.f;
+      }
+    }
     const int k0 = single ? 0 : (c_b / bpc) * KC;
 #pragma unroll
-    for (int j = 0; j < GEMM_NB; ++j) {
+    for (int j = 0; j < NBK; ++j) {
       const int kl = c_b * SPAN + j * BK + lane * VEC - k0;    // < KC
       float xf[MT][VEC];
 #pragma unroll
@@ -327,7 +437,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G,
         }
       }
 #pragma unroll
-      for (int r = 0; r < GEMM_WROWS; ++r) {
+      for (int r = 0; r < WR; ++r) {
         float wf[VEC];
         WTr<WT>::unpack(cur[j][r], wf);
 #pragma unroll
@@ -339,11 +449,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G,
     if (c_b == nbps - 1) {
       // the set is complete: cross-lane reduction and epilogue
 #pragma unroll
-      for (int r = 0; r < GEMM_WROWS; ++r)
+      for (int r = 0; r < WR; ++r)
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[r][m] = wave_sum(acc[r][m]);
       const int s = gw + c_it * nwaves;
-      if (lane == 0 && s < nsets) {
+      if (lane == 0 && c_it < nmine) {
 #pragma unroll
         for (int r = 0; r < LR; ++r) {
           int n = s * LR + r;
@@ -353,34 +463,35 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G,
             if (m >= M) continue;
             float y;
             if (PAIRED) {
-              float gt = acc[2 * r][m], up = acc[2 * r + 1][m];
-              if (G.B[0]) gt += WTr<WT>::load1(G.B[0], n);
-              if (G.B[1]) up += WTr<WT>::load1(G.B[1], n);
-              y = silu(gt) * up;
+              y = silu(acc[2 * r][m] + pb[2 * r]) * (acc[2 * r + 1][m] + pb[2 * r + 1]);
             } else {
-              y = acc[r][m];
-              int seg = 0, loc = n;
-              if (loc >= a.N[0]) { loc -= a.N[0]; seg = 1; if (loc >= a.N[1]) { loc -= a.N[1]; seg = 2; } }
-              if (G.B[seg]) y += WTr<WT>::load1(G.B[seg], loc);
+              y = acc[r][m] + pb[r];
               if (a.act == 1) y = gelu_erf(y);
               else if (a.act == 2) y = fmaxf(y, 0.f);
             }
-            if (G.Rsd) y += G.Rsd[(size_t)m * a.ldy + n];
+            y += prs[r][m];
             G.Y[(size_t)m * a.ldy + n] = y;
             if (a.topk > 0 && m == 0) hlog[(c_it * GEMM_WAVES + wave) * LR + r] = y;
           }
         }
       }
 #pragma unroll
-      for (int r = 0; r < GEMM_WROWS; ++r)
+      for (int r = 0; r < WR; ++r)
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[r][m] = 0.f;
     }
   };
-  for (int q = 0; q < Q; q += 2) {
-    step(q, bufA, bufB);
-    if (q + 1 < Q) step(q + 1, bufB, bufA);
+  // one request and one batch of arithmetic per step, buffers rotating
+  int q = 0;
+  for (; q + 4 <= Q; q += 4) {
+    issue_next(b3); step(q, b0);
+    issue_next(b0); step(q + 1, b1);
+    issue_next(b1); step(q + 2, b2);
+    issue_next(b2); step(q + 3, b3);
   }
+  if (q < Q) { issue_next(b3); step(q, b0); }
+  if (q + 1 < Q) { issue_next(b0); step(q + 1, b1); }
+  if (q + 2 < Q) { issue_next(b1); step(q + 2, b2); }
 
   // ---- LM head: this workgroup's top-k by (logit descending, id ascending)
   if (a.topk > 0) {
@@ -414,12 +525,12 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const GemmGroup& G,
 }
 
 // MA rows in group 0, MB rows in group 1 (MB == 0: single-group launch)
-template <typename WT, int MA, int MB, bool PAIRED>
+template <typename WT, int MA, int MB, bool PAIRED, int WR>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs a) {
   extern __shared__ float4 lds4[];
   float* lds = (float*)lds4;
-  if (MB == 0 || blockIdx.y == 0) gemm_body<WT, MA, PAIRED>(a, a.g[0], lds);
-  else gemm_body<WT, (MB < 1 ? 1 : MB), PAIRED>(a, a.g[1], lds);
+  if (MB == 0 || blockIdx.y == 0) gemm_body<WT, MA, PAIRED, WR>(a, a.g[0], lds);
+  else gemm_body<WT, (MB < 1 ? 1 : MB), PAIRED, WR>(a, a.g[1], lds);
 }
 
 // ------------------------------------------------------------------ attention
@@ -630,6 +741,7 @@ struct MergeArgs {
   const DevState* ds;
   int H, HD, d_model, nchunk_max;
 };
+#ifdef PPD_ENGINE_TU
 __global__ void attn_merge_kernel(MergeArgs a) {
   int g = blockIdx.z, h = blockIdx.y, m = blockIdx.x;
   if (m >= a.M[g]) return;
@@ -648,6 +760,7 @@ __global__ void attn_merge_kernel(MergeArgs a) {
   }
   a.out[g][(size_t)m * a.d_model + (size_t)h * a.HD + i] = o / l;
 }
+#endif
 
 // ------------------------------------------------------------------ selection
 // Early prediction: top-k of the early logits by (logit descending, id ascending); the head GEMM
