@@ -51,7 +51,7 @@ typedef struct {
   int32_t act;       /* 0 GELU (erf form), 1 ReLU, 2 SwiGLU */
   int32_t pos;       /* 0 learned absolute position table, 1 RoPE (rotate-half pairs i, i+head_dim/2) */
   int32_t has_bias;  /* linear layers carry biases */
-  int32_t wdtype;    /* 0 fp32, 1 bf16: type of every weight tensor and of the KV cache */
+  int32_t wdtype;    /* 0 fp32, 1 bf16: type of every weight tensor (activations and the KV cache are fp32) */
   float norm_eps;
   float rope_theta;
   int32_t eos_id;    /* -1: never stop */
@@ -162,13 +162,14 @@ int ppd_get_early_logits(ppd_ctx *ctx, float *host_logits);
 /* Copy the counters (HOST). */
 int ppd_get_stats(const ppd_ctx *ctx, ppd_stats *out);
 
-/* Per-kernel timing with HIP events on the context's stream.  While enabled
- * every launch is bracketed by two events; ppd_get_kernel_time returns, for
- * one kernel class and one launch shape (groups = 1: one row group, the main
- * token alone; groups = 2: a pipelined step's launch, main row + k candidate
- * rows), the summed elapsed milliseconds and the number of launches since
- * profiling was enabled (HOST outputs).  Prefill is never profiled. */
-int ppd_set_profiling(ppd_ctx *ctx, int on);
+/* Timing with HIP events on the context's streams.  level 2: every launch is bracketed by two
+ * events; level 1: only the phases of a round are (class PPD_KC_PHASE), so the kernels run
+ * back to back as in normal operation; level 0: off.  While on, rounds are issued eagerly
+ * instead of replayed from graphs.  ppd_get_kernel_time returns, for one class and one launch
+ * shape (groups = 1: one row group; groups = 2: a two-group launch, or for PPD_KC_PHASE the
+ * whole parallel phase), the summed elapsed milliseconds and the number of brackets since
+ * profiling was switched on (HOST outputs).  Prefill is never profiled. */
+int ppd_set_profiling(ppd_ctx *ctx, int level);
 /* Rounds are replayed as captured HIP graphs (one per round shape) unless profiling is on;
  * on = 0 issues every launch eagerly instead.  Results are identical either way. */
 int ppd_set_graphs(ppd_ctx *ctx, int on);

@@ -198,8 +198,8 @@ class PPD:
         self._chk(load_library().ppd_get_stats(self._h, ctypes.byref(s)), "ppd_get_stats")
         return {n: int(getattr(s, n)) for n, _ in Stats._fields_}
 
-    def ppd_set_profiling(self, on: bool):
-        self._chk(load_library().ppd_set_profiling(self._h, int(on)), "ppd_set_profiling")
+    def ppd_set_profiling(self, level: int):
+        self._chk(load_library().ppd_set_profiling(self._h, int(level)), "ppd_set_profiling")
 
     def ppd_set_graphs(self, on: bool):
         self._chk(load_library().ppd_set_graphs(self._h, int(on)), "ppd_set_graphs")

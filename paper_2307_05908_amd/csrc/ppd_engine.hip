@@ -32,7 +32,8 @@ struct ppd_ctx {
   hipStream_t cur;           // stream the launch helpers issue to
   hipEvent_t join_ev, fork_ev, back_ev;
   int dual;                  // parallel phase as two concurrent chains (1) or as two-group launches (0)
-  int wbytes;
+  int wbytes;                // bytes per weight element
+  static constexpr int kvbytes = 4;   // keys and values are cached in fp32, like every other activation
   // weights (borrowed)
   const void *tok_emb, *pos_emb, *lnf_g, *lnf_b, *lm_head, *early_head;
   std::vector<LayerW> L;
@@ -88,11 +89,12 @@ int g_create_hip_error = 0;   // hipError_t of the last ppd_create that failed w
     }                                           \
   } while (0)
 
-inline size_t cache_layer_bytes(const ppd_ctx* c) { return (size_t)c->d.max_ctx * c->d.d_model * c->wbytes; }
+inline size_t cache_layer_bytes(const ppd_ctx* c) { return (size_t)c->d.max_ctx * c->d.d_model * c->kvbytes; }
 
 struct ProfScope {
   ppd_ctx* c; int cls; size_t idx; bool on; hipStream_t st = nullptr;
-  ProfScope(ppd_ctx* c_, int cls_, int groups = 1) : c(c_), cls(cls_ + (groups - 1) * PPD_KC_COUNT), idx(0), on(c_->prof != 0) {
+  ProfScope(ppd_ctx* c_, int cls_, int groups = 1)
+      : c(c_), cls(cls_ + (groups - 1) * PPD_KC_COUNT), idx(0), on(c_->prof >= 2 || (c_->prof == 1 && cls_ == PPD_KC_PHASE)) {
     if (!on) return;
     if (c->ev_used + 2 > c->ev.size()) {
       for (int i = 0; i < 2; ++i) { hipEvent_t e; if (hipEventCreate(&e) != hipSuccess) { on = false; return; } c->ev.push_back(e); }
@@ -175,12 +177,8 @@ hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups, int pmax) {
   dim3 grid(pmax / ATT_CHUNK + 1, a.H, ngroups);
   int MB = ngroups == 2 ? a.g[1].M : 0;
   const int MA = a.g[0].M;
-  if (c->wbytes == 4) {
-    if (c->d.head_dim == 64) return launch_attn_t<float, 64>(c->cur, a, MA, MB, grid);
-    return launch_attn_t<float, 128>(c->cur, a, MA, MB, grid);
-  }
-  if (c->d.head_dim == 64) return launch_attn_t<bf16_t, 64>(c->cur, a, MA, MB, grid);
-  return launch_attn_t<bf16_t, 128>(c->cur, a, MA, MB, grid);
+  if (c->d.head_dim == 64) return launch_attn_t<float, 64>(c->cur, a, MA, MB, grid);
+  return launch_attn_t<float, 128>(c->cur, a, MA, MB, grid);
 }
 
 // A row group of one layer step: which layer, how many rows, first row in the
@@ -227,7 +225,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
       G.Kc = c->Kc + (size_t)l * cache_layer_bytes(c);
       G.Vc = c->Vc + (size_t)l * cache_layer_bytes(c);
       if (rg[g].tail) {
-        size_t off = (size_t)l * c->k * dm * c->wbytes;
+        size_t off = (size_t)l * c->k * dm * c->kvbytes;
         G.ownK = c->tailK + off; G.ownV = c->tailV + off;
         G.own_row_stride = dm; G.own_head_stride = d.head_dim; G.own_cache = 0;
       } else {
@@ -345,7 +343,7 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     grid = dim3((d.d_model + SEL_THREADS - 1) / SEL_THREADS, c->k);
   } else if (adopt) {
     s.h = c->h; s.tailK = c->tailK; s.tailV = c->tailV; s.Kc = c->Kc; s.Vc = c->Vc;
-    s.nb = c->nb; s.H = d.n_heads; s.hd = d.head_dim; s.d_model = d.d_model; s.max_ctx = d.max_ctx; s.wbytes = c->wbytes;
+    s.nb = c->nb; s.H = d.n_heads; s.hd = d.head_dim; s.d_model = d.d_model; s.max_ctx = d.max_ctx; s.wbytes = c->kvbytes;
     grid = dim3(c->nb, 2);
   }
   ProfScope ps(c, PPD_KC_SELECT);
@@ -452,7 +450,7 @@ void account_round(ppd_ctx* c, int kind, int pos) {
   const ppd_model_dims& d = c->d;
   const uint64_t wl = ((uint64_t)4 * d.d_model * d.d_model + (uint64_t)(d.act == 2 ? 3 : 2) * d.d_model * d.d_ff) * c->wbytes;
   const uint64_t wh = (uint64_t)d.vocab * d.d_model * c->wbytes;
-  const uint64_t kvp = (uint64_t)2 * d.d_model * c->wbytes;     // K and V of one position of one layer
+  const uint64_t kvp = (uint64_t)2 * d.d_model * c->kvbytes;    // K and V of one position of one layer
   if (kind == 2) {
     c->st.weight_bytes += d.n_layers * wl + wh;
     c->st.kv_bytes += (uint64_t)d.n_layers * pos * kvp;
@@ -551,8 +549,8 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   auto alloc = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
   alloc((void**)&c->Kc, (size_t)d.n_layers * cache_layer_bytes(c));
   alloc((void**)&c->Vc, (size_t)d.n_layers * cache_layer_bytes(c));
-  alloc((void**)&c->tailK, (size_t)c->nb * k * dm * c->wbytes);
-  alloc((void**)&c->tailV, (size_t)c->nb * k * dm * c->wbytes);
+  alloc((void**)&c->tailK, (size_t)c->nb * k * dm * c->kvbytes);
+  alloc((void**)&c->tailV, (size_t)c->nb * k * dm * c->kvbytes);
   alloc((void**)&c->h, R * dm * sizeof(float));
   alloc((void**)&c->qkv, R * 3 * dm * sizeof(float));
   alloc((void**)&c->att, R * dm * sizeof(float));
@@ -703,7 +701,7 @@ int ppd_get_stats(const ppd_ctx* c, ppd_stats* out) {
 int ppd_set_profiling(ppd_ctx* c, int on) {
   if (!c) return PPD_EINVAL;
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  c->prof = on ? 1 : 0;
+  c->prof = on < 0 ? 0 : (on > 2 ? 2 : on);
   c->ev_used = 0;
   if (on) { memset(c->kc_ms, 0, sizeof c->kc_ms); memset(c->kc_n, 0, sizeof c->kc_n); }
   return PPD_OK;

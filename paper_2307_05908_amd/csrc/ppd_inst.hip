@@ -73,10 +73,8 @@ hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int MA, int MB, 
 
 
 #if PPD_INST == 8
-template hipError_t launch_attn_t<bf16_t, 128>(hipStream_t, const AttnArgs&, int, int, dim3);
-template hipError_t launch_attn_t<bf16_t, 64>(hipStream_t, const AttnArgs&, int, int, dim3);
-#elif PPD_INST == 9
 template hipError_t launch_attn_t<float, 128>(hipStream_t, const AttnArgs&, int, int, dim3);
+#elif PPD_INST == 9
 template hipError_t launch_attn_t<float, 64>(hipStream_t, const AttnArgs&, int, int, dim3);
 #endif
 #endif

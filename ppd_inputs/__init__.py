@@ -106,7 +106,7 @@ class ModelConfig:
         return self.vocab * self.d_model * self.wbytes
 
     def kv_bytes_per_pos_layer(self) -> int:
-        return 2 * self.d_model * self.wbytes
+        return 2 * self.d_model * 4      # keys and values are cached in fp32
 
 
 CONFIGS: Dict[str, ModelConfig] = {
