@@ -21,6 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+# HBM bytes per launch of the roofline kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of
+# known size (profiles/llama7b_ppd_k3_kernels.txt); only valid for the configuration it was collected on
+MEASURED_TRAFFIC = {"llama7b": 181.09e6}
 
 
 def main():
@@ -34,6 +37,8 @@ def main():
     ap.add_argument("--prompt", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=32)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the pipelined decode step of one sequence "
@@ -75,6 +80,13 @@ def main():
         wall = time.perf_counter() - t
         return wall, ev0.elapsed_time(ev1) / 1e3
 
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- PPD rounds
     P = binding.PPD(cfg, dev, k=k, exit_layer=e)
     wall_ppd, _ = timed(P, lambda: P.ppd_step(want_info=False), W, K)
@@ -115,7 +127,8 @@ def main():
         avg_s = dom["ms"] / dom["launches"] / 1e3
         ach = ffn_in_bytes / avg_s / 1e9
         roof = {"bound": "hbm", "kernel": "gemm_kernel (norm + FFN-in matrices + activation), one row", "achieved": round(ach, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC.get(cfg.name) if cfg.name.startswith("llama7b") else None,
                 "bytes_per_launch": ffn_in_bytes, "avg_launch_us": round(avg_s * 1e6, 2)}
     pp = ph.get("phase.g2")
     pipe = None
