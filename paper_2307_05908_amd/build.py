@@ -19,7 +19,7 @@ DEPS = [os.path.join(CSRC, f) for f in ("ppd_engine.hip", "ppd_inst.hip", "ppd_k
 # -ffp-contract=off: every fused multiply-add in the kernels is an explicit fmaf, so a row's arithmetic
 # does not depend on which template instance it runs in.  Packed-fp32 code generation is switched off.
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-variable"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-variable", "-Wno-inline-asm"]
 
 
 def stale() -> bool:

@@ -37,6 +37,13 @@ struct ppd_ctx {
   // weights (borrowed)
   const void *tok_emb, *pos_emb, *lnf_g, *lnf_b, *lm_head, *early_head;
   std::vector<LayerW> L;
+  // bf16 models: weights repacked into MFMA blocks (owned copies); fp32 models stream the caller's tensors
+  int mfma;
+  int mg_occ;            // workgroups of the MFMA GEMM a compute unit is asked to hold (1 or 2)
+  struct LayerP { void *qkv, *o, *fin, *fout; };
+  std::vector<LayerP> LP;
+  void *head_p, *early_p;
+  std::vector<void*> owned;   // every repacked buffer, for ppd_destroy
   // device memory owned by the context
   char *Kc, *Vc;         // [L][H][max_ctx][hd]
   char *tailK, *tailV;   // [nb][k][H][hd]
@@ -171,6 +178,63 @@ hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
                 : launch_gemm_t<bf16_t, false, 2>(c->cur, a, MA, MB, grid, lds);
 }
 
+// ---- bf16 models: MFMA GEMM on repacked weights
+constexpr size_t MG_LDS_MAX = 160 * 1024;
+
+// One logical GEMM for one or two row groups.  Everything goes into one launch when the staged rows of
+// the largest group fit LDS; otherwise every group is launched on its own, its rows in slices that fit
+// (each slice streams the weights again).
+hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
+  a.KT = (a.K + 31) / 32;
+  a.xrow = mg_xrow(a.KT);
+  if ((size_t)a.NT * a.KT * 1024 > 0x7fffffffu) return hipErrorInvalidValue;   // 32-bit offsets into one matrix
+  a.wbytes = (unsigned)((size_t)a.NT * a.KT * 1024);
+  auto lds_for = [&](int M, int tiles) { int b, p, x; return (size_t)mg_lds_layout(a.K, M, a.norm, tiles, a.xrow, b, p, x); };
+  // Workgroups per group: the launch's share of the machine (two workgroups of 8 waves fit a compute
+  // unit when their LDS does), then the smallest grid with the same number of tiles per workgroup, so
+  // that all of them finish together.
+  auto go = [&](MGemmArgs x, int ng, int mm) -> hipError_t {
+    int gx;
+    if (x.topk > 0) gx = c->head_grid;
+    else {
+      const int share = (ng == 2 || c->in_dual) ? 2 : 1;
+      int per_cu = c->mg_occ;
+      int gmax = 256 * per_cu / share;
+      int t = (x.NT + gmax - 1) / gmax;
+      if (per_cu > 1 && lds_for(mm, t) * per_cu > MG_LDS_MAX) { gmax = 256 / share; t = (x.NT + gmax - 1) / gmax; }
+      gx = (x.NT + t - 1) / t;
+    }
+    if (gx > x.NT) gx = x.NT;
+    x.tiles_wg = (x.NT + gx - 1) / gx;
+    const size_t lds = lds_for(mm, x.tiles_wg);
+    if (lds > MG_LDS_MAX || (x.topk > 0 && x.tiles_wg * 16 > HEAD_MAX_ROWS)) return hipErrorInvalidValue;
+    dim3 grid(gx, ng);
+    if (paired) hipLaunchKernelGGL(gemm_mfma_kernel<true>, grid, dim3(MG_THREADS), lds, c->cur, x);
+    else hipLaunchKernelGGL(gemm_mfma_kernel<false>, grid, dim3(MG_THREADS), lds, c->cur, x);
+    return hipGetLastError();
+  };
+  int mmax = a.g[0].M;
+  if (ngroups == 2 && a.g[1].M > mmax) mmax = a.g[1].M;
+  // rows whose staged form fits LDS next to the partial sums of a one-workgroup-per-unit grid
+  const int t1 = a.topk > 0 ? (a.NT + c->head_grid - 1) / c->head_grid : (a.NT + 255) / 256;
+  int mcap = 0;
+  while (mcap < 16 && lds_for(mcap + 1, t1 * 2) <= MG_LDS_MAX) ++mcap;
+  if (mmax <= mcap) return go(a, ngroups, mmax);
+  if (mcap < 1) return hipErrorInvalidValue;
+  for (int g = 0; g < ngroups; ++g) {
+    for (int r0 = 0; r0 < a.g[g].M; r0 += mcap) {
+      MGemmArgs x = a;
+      MGemmGroup G = a.g[g];
+      const int mc = G.M - r0 < mcap ? G.M - r0 : mcap;
+      G.X += (size_t)r0 * a.ldx; G.Y += (size_t)r0 * a.ldy; if (G.Rsd) G.Rsd += (size_t)r0 * a.ldy; G.M = mc;
+      x.g[0] = G;
+      hipError_t e = go(x, 1, mc);
+      if (e != hipSuccess) return e;
+    }
+  }
+  return hipSuccess;
+}
+
 // pmax: largest position any row of the launch sits at (host-side bound for the grid; the kernel
 // itself reads the position from the device state and idle chunks return at once)
 hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups, int pmax) {
@@ -179,6 +243,22 @@ hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups, int pmax) {
   const int MA = a.g[0].M;
   if (c->d.head_dim == 64) return launch_attn_t<float, 64>(c->cur, a, MA, MB, grid);
   return launch_attn_t<float, 128>(c->cur, a, MA, MB, grid);
+}
+
+// the same launch described for the MFMA kernel: P[g] = group g's repacked weights
+hipError_t mgemm_from(ppd_ctx* c, const GemmArgs& a, int ngroups, bool paired, void* const* P) {
+  MGemmArgs m; memset(&m, 0, sizeof m);
+  for (int g = 0; g < ngroups; ++g) {
+    const GemmGroup& s = a.g[g];
+    MGemmGroup& t = m.g[g];
+    t.X = s.X; t.Rsd = s.Rsd; t.Y = s.Y; t.P = P[g];
+    t.B[0] = s.B[0]; t.B[1] = s.B[1]; t.B[2] = s.B[2]; t.ng = s.ng; t.nb = s.nb; t.M = s.M;
+  }
+  m.K = a.K; m.N[0] = a.N[0]; m.N[1] = a.N[1]; m.N[2] = a.N[2]; m.ntot = a.ntot;
+  m.NT = paired ? (a.ntot + 7) / 8 : (a.ntot + 15) / 16;
+  m.ldx = a.ldx; m.ldy = a.ldy; m.norm = a.norm; m.eps = a.eps; m.act = a.act == 3 ? 0 : a.act;
+  m.topk = a.topk; m.pk_val = a.pk_val; m.pk_idx = a.pk_idx;
+  return launch_mgemm(c, m, ngroups, paired);
 }
 
 // A row group of one layer step: which layer, how many rows, first row in the
@@ -211,6 +291,10 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     a.K = dm; a.N[0] = a.N[1] = a.N[2] = dm; a.ntot = 3 * dm; a.ldx = dm; a.ldy = 3 * dm;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
     ProfScope ps(c, PPD_KC_GEMM_QKV, ngroups);
+    if (c->mfma) {
+      void* P[2] = {c->LP[rg[0].layer].qkv, ngroups == 2 ? c->LP[rg[1].layer].qkv : nullptr};
+      HIPCHK(c, mgemm_from(c, a, ngroups, false, P));
+    } else
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   // 2. RoPE + KV write + attention partials, then merge
@@ -259,6 +343,10 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     }
     a.K = dm; a.N[0] = dm; a.ntot = dm; a.ldx = dm; a.ldy = dm; a.norm = -1; a.act = 0;
     ProfScope ps(c, PPD_KC_GEMM_O, ngroups);
+    if (c->mfma) {
+      void* P[2] = {c->LP[rg[0].layer].o, ngroups == 2 ? c->LP[rg[1].layer].o : nullptr};
+      HIPCHK(c, mgemm_from(c, a, ngroups, false, P));
+    } else
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   // 4. norm2 + FFN in (+ gate/up pairing) + activation
@@ -276,6 +364,10 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     a.K = dm; a.N[0] = F; a.N[1] = swiglu ? F : 0; a.ntot = F; a.ldx = dm; a.ldy = F;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = swiglu ? 3 : (d.act == 0 ? 1 : 2);
     ProfScope ps(c, PPD_KC_GEMM_FFN_IN, ngroups);
+    if (c->mfma) {
+      void* P[2] = {c->LP[rg[0].layer].fin, ngroups == 2 ? c->LP[rg[1].layer].fin : nullptr};
+      HIPCHK(c, mgemm_from(c, a, ngroups, swiglu, P));
+    } else
     HIPCHK(c, launch_gemm(c, a, ngroups, swiglu));
   }
   // 5. FFN out + residual
@@ -289,6 +381,10 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     }
     a.K = F; a.N[0] = dm; a.ntot = dm; a.ldx = F; a.ldy = dm; a.norm = -1; a.act = 0;
     ProfScope ps(c, PPD_KC_GEMM_FFN_OUT, ngroups);
+    if (c->mfma) {
+      void* P[2] = {c->LP[rg[0].layer].fout, ngroups == 2 ? c->LP[rg[1].layer].fout : nullptr};
+      HIPCHK(c, mgemm_from(c, a, ngroups, false, P));
+    } else
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   return PPD_OK;
@@ -332,6 +428,10 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
     a.topk = early ? c->k : 1; a.pk_val = c->pk_val; a.pk_idx = c->pk_idx;
     ProfScope ps(c, PPD_KC_HEAD);
+    if (c->mfma) {
+      void* P[2] = {(early && c->early_p) ? c->early_p : c->head_p, nullptr};
+      HIPCHK(c, mgemm_from(c, a, 1, false, P));
+    } else
     HIPCHK(c, launch_gemm(c, a, 1, false));
   }
   SelectArgs s; memset(&s, 0, sizeof s);
@@ -466,6 +566,7 @@ void free_all(ppd_ctx* c) {
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
                  c->early_logits, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
+  for (void* p : c->owned) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   if (c->join_ev) (void)hipEventDestroy(c->join_ev);
@@ -558,8 +659,9 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   alloc((void**)&c->part, R * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
   alloc((void**)&c->logits, (size_t)d.vocab * sizeof(float));
   alloc((void**)&c->early_logits, (size_t)d.vocab * sizeof(float));
-  alloc((void**)&c->pk_val, (size_t)c->head_grid * MAXM * sizeof(float));
-  alloc((void**)&c->pk_idx, (size_t)c->head_grid * MAXM * sizeof(int32_t));
+  const size_t pk_slots = (size_t)(c->head_grid > (d.vocab + 255) / 256 ? c->head_grid : (d.vocab + 255) / 256) + 1024;   // room for either head grid
+  alloc((void**)&c->pk_val, pk_slots * MAXM * sizeof(float));
+  alloc((void**)&c->pk_idx, pk_slots * MAXM * sizeof(int32_t));
   alloc((void**)&c->ds, sizeof(DevState));
   alloc((void**)&c->prompt_dev, (size_t)d.max_ctx * sizeof(int32_t));
   if (d.pos == 1) alloc((void**)&c->rope, (size_t)d.max_ctx * (d.head_dim / 2) * sizeof(float2));
@@ -583,6 +685,49 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     e = hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
   }
   if (e == hipSuccess) e = hipMemset(c->ds, 0, sizeof(DevState));
+  c->mfma = d.wdtype == 1 && env_int("PPD_MFMA", 1) != 2;
+  if (e == hipSuccess && c->mfma) {
+    // repack every linear weight into MFMA blocks (owned copies)
+    auto repack = [&](const void* s0, const void* s1, const void* s2, int n0, int n1, int n2, int K, bool paired, void** out) {
+      if (e != hipSuccess) return;
+      RepackArgs r; memset(&r, 0, sizeof r);
+      r.src[0] = (const uint16_t*)s0; r.src[1] = (const uint16_t*)s1; r.src[2] = (const uint16_t*)s2;
+      r.nrows[0] = n0; r.nrows[1] = n1; r.nrows[2] = n2; r.K = K; r.KT = (K + 31) / 32; r.paired = paired ? 1 : 0;
+      const int rows = paired ? n0 : n0 + n1 + n2;
+      r.NT = paired ? (rows + 7) / 8 : (rows + 15) / 16;
+      void* dst = nullptr;
+      e = hipMalloc(&dst, (size_t)r.NT * r.KT * 1024);
+      if (e != hipSuccess) return;
+      c->owned.push_back(dst);
+      r.dst = (uint16_t*)dst;
+      hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(r.NT * r.KT)), dim3(64), 0, 0, r);
+      e = hipGetLastError();
+      *out = dst;
+    };
+    c->LP.resize(d.n_layers);
+    for (int l = 0; l < d.n_layers; ++l) {
+      const LayerW& x = c->L[l];
+      repack(x.wq, x.wk, x.wv, (int)dm, (int)dm, (int)dm, (int)dm, false, &c->LP[l].qkv);
+      repack(x.wo, nullptr, nullptr, (int)dm, 0, 0, (int)dm, false, &c->LP[l].o);
+      if (d.act == 2) repack(x.w_in, x.w_up, nullptr, d.d_ff, d.d_ff, 0, (int)dm, true, &c->LP[l].fin);
+      else repack(x.w_in, nullptr, nullptr, d.d_ff, 0, 0, (int)dm, false, &c->LP[l].fin);
+      repack(x.w_out, nullptr, nullptr, (int)dm, 0, 0, d.d_ff, false, &c->LP[l].fout);
+    }
+    repack(c->lm_head, nullptr, nullptr, d.vocab, 0, 0, (int)dm, false, &c->head_p);
+    if (c->early_head) repack(c->early_head, nullptr, nullptr, d.vocab, 0, 0, (int)dm, false, &c->early_p);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
+    // head launches: the same balanced grid as any other GEMM; a workgroup keeps at most
+    // HEAD_MAX_ROWS logits = 16 tiles
+    c->mg_occ = env_int("PPD_MGOCC", 1) == 2 ? 2 : 1;
+    const int NTh = (d.vocab + 15) / 16;
+    int th = (NTh + 256 * c->mg_occ - 1) / (256 * c->mg_occ);
+    c->head_grid = (NTh + th - 1) / th;
+    while ((NTh + c->head_grid - 1) / c->head_grid > HEAD_MAX_ROWS / 16) ++c->head_grid;
+    if ((size_t)c->head_grid > pk_slots) e = hipErrorInvalidValue;
+    if (env_int("PPD_DUAL", 2) != 1) c->dual = 0;   // one launch per step for both chains unless asked otherwise
+  }
   if (e != hipSuccess) {
     g_create_hip_error = (int)e;
     (void)hipGetLastError();

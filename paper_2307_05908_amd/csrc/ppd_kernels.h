@@ -878,3 +878,390 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
 }
 
 }  // namespace ppd
+
+// ==================================================================== bf16 weights: MFMA path
+// For bf16 models every linear weight is repacked once (at context creation) into blocks that are
+// both one contiguous kilobyte in HBM and one A operand of v_mfma_f32_16x16x32_bf16: block (nt, kt)
+// holds rows 16*nt .. 16*nt+15, columns 32*kt .. 32*kt+31; inside it lane l = i + 16*c owns the eight
+// consecutive bf16 of row i, columns 8*c .. 8*c+7.  A wave-load is then a flat 1 KiB read, needs no
+// unpacking, and a skinny GEMM with up to 16 rows costs the same as with one: the candidates' rows
+// ride along in the B operand's other columns.
+//
+// The B operand carries the input rows split into two bf16 terms, x = hi + lo with hi = bf16(x) and
+// lo = bf16(x - hi) (|x - hi - lo| <= 2^-17 |x|), so the products are exact in fp32 and the fp32
+// activations keep 16 mantissa bits.
+//
+// The kernel is built around instruction count: at 8 TB/s a compute unit has about 80 cycles per
+// kilobyte block, i.e. some twenty vector instructions per block and wave.  Everything that is the
+// same for a whole wave lives in scalar registers (the wave index goes through readfirstlane), the
+// weight stream uses buffer loads (scalar base + scalar offset + one lane offset), the input rows come
+// into LDS with direct-to-LDS loads, and the main loop has no barrier: every wave streams its eighth
+// of the reduction length of all the workgroup's tiles and leaves its partial sums in LDS; one
+// barrier, then the epilogue adds the eight partials of every output in wave order.
+namespace ppd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int MG_THREADS = 512;     // 8 waves: each takes one eighth of the reduction length of a 16-row tile
+constexpr int MG_WAVES = MG_THREADS / WAVE;
+constexpr int MG_BATCH = 4;         // 1 KiB blocks requested per register batch
+constexpr int MG_RING = 4;          // register batches in flight per wave
+constexpr int MG_EP = 2;            // outputs per thread whose bias and residual are requested in the prologue
+constexpr int MG_LDS_HLOG = 2048;   // byte offsets: [0, 2048) norm statistics, then 1 KiB of head logits,
+constexpr int MG_LDS_G = 3072;      // then the norm's gain (and bias), the partial sums, the staged rows
+
+struct RepackArgs {
+  const uint16_t* src[3]; int nrows[3];   // up to three row segments, concatenated (Q | K | V); paired: src[0] gate, src[1] up
+  int K, KT, NT, paired;
+  uint16_t* dst;
+};
+#ifdef PPD_ENGINE_TU
+__global__ void repack_kernel(RepackArgs a) {
+  // one workgroup of 64 lanes per block
+  const int blk = blockIdx.x, lane = threadIdx.x;
+  const int nt = blk / a.KT, kt = blk - nt * a.KT;
+  const int i = lane & 15, c = lane >> 4;
+  const uint16_t* row = nullptr;
+  if (a.paired) {
+    int n = nt * 8 + (i & 7);
+    if (n < a.nrows[0]) row = a.src[i < 8 ? 0 : 1] + (size_t)n * a.K;
+  } else {
+    int n = nt * 16 + i, seg = 0;
+    while (seg < 3 && n >= a.nrows[seg]) { n -= a.nrows[seg]; ++seg; }
+    if (seg < 3) row = a.src[seg] + (size_t)n * a.K;
+  }
+  uint16_t v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    int k = kt * 32 + c * 8 + e;
+    v[e] = (row && k < a.K) ? row[k] : (uint16_t)0;
+  }
+  uint4 o;
+  o.x = v[0] | ((uint32_t)v[1] << 16); o.y = v[2] | ((uint32_t)v[3] << 16);
+  o.z = v[4] | ((uint32_t)v[5] << 16); o.w = v[6] | ((uint32_t)v[7] << 16);
+  *(uint4*)(a.dst + ((size_t)blk * 64 + lane) * 8) = o;
+}
+#endif
+
+struct MGemmGroup {
+  const float* X;     // [M][ldx] input rows (before the fused norm), rows 16-byte aligned
+  const float* Rsd;   // residual rows [M][ldy] added in the epilogue, or null
+  float* Y;           // [M][ldy]
+  const void* P;      // repacked weights [NT][KT][64 lanes][8 bf16]
+  const void* B[3];   // biases per row segment or null (paired: B[0] gate, B[1] up)
+  const void* ng; const void* nb;  // gain / bias of the fused norm
+  int M;              // rows, 1..16
+};
+struct MGemmArgs {
+  MGemmGroup g[2];
+  int K, KT, NT;    // reduction length (multiple of 8), its 32-column blocks, 16-row tiles
+  int N[3];         // rows per segment (bias lookup)
+  int ntot;         // logical output rows (paired: rows of one of the two matrices)
+  int ldx, ldy;
+  int norm;         // -1 none, 0 LayerNorm, 1 RMSNorm
+  float eps;
+  int act;          // 0 none, 1 GELU, 2 ReLU (paired launches apply SwiGLU)
+  int topk; float* pk_val; int32_t* pk_idx;
+  int xrow;         // LDS bytes between two staged rows
+  int tiles_wg;     // ceil(NT / gridDim.x); gridDim.x <= NT
+  unsigned wbytes;  // NT * KT * 1024
+};
+
+// LDS bytes between staged rows: the row itself, moved off a multiple of 256 so that neighbouring rows
+// start in different banks
+__host__ __device__ inline int mg_xrow(int KT) { int r = KT * 128; return (r & 255) ? r : r + 128; }
+// LDS map behind MG_LDS_G; returns the total
+__host__ __device__ inline int mg_lds_layout(int K, int M, int norm, int tiles_wg, int xrow, int& off_b, int& off_part, int& off_x) {
+  const int gsz = (K * 2 + 1023) & ~1023;
+  off_b = MG_LDS_G + (norm >= 0 ? gsz : 0);
+  off_part = off_b + (norm == 0 ? gsz : 0);
+  off_x = off_part + tiles_wg * MG_WAVES * M * 64;
+  return off_x + M * xrow;
+}
+
+// 64 lanes x 16 bytes from per-lane global addresses to LDS at lds_dst + 16 * lane (lds_dst is the same
+// for the whole wave and goes through M0).  Written as assembly so that the wait for it stays ours:
+// the request counts in vmcnt like any load, and loads return in order.
+__device__ __forceinline__ void dma16(const void* src, void* lds_dst) {
+  const unsigned la = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst;
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(la) : "memory", "m0");
+}
+
+template <bool PAIRED>
+__global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
+  extern __shared__ float4 lds4[];
+  char* lds = (char*)lds4;
+  const MGemmGroup& G = a.g[blockIdx.y];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int M = G.M, K = a.K, KT = a.KT;
+  const int grid = gridDim.x, xrow = a.xrow;
+  const int ntiles = (int)blockIdx.x + (a.tiles_wg - 1) * grid < a.NT ? a.tiles_wg : a.tiles_wg - 1;
+  int off_b, off_part, off_x;
+  mg_lds_layout(K, M, a.norm, a.tiles_wg, xrow, off_b, off_part, off_x);
+  float* stat = (float*)lds;                  // mu[16], rstd[16], redA[16][8], redB[16][8]
+  float* redA = stat + 32;
+  float* redB = stat + 32 + 16 * MG_WAVES;
+  float* hlog = (float*)(lds + MG_LDS_HLOG);
+
+  // ---- 1. input rows (and the norm's gain and bias) into LDS, fp32 as they are: wave w takes the
+  // kilobyte pieces w, w + 8, ... of every row.  These requests come first: a wave's loads return in order.
+  {
+    const int U = (K + 255) >> 8;
+    for (int m = 0; m < M; ++m)
+      for (int u = wave; u < U; u += MG_WAVES) {
+        const int kk = u * 256 + lane * 4;
+        if (kk < K) dma16(G.X + (size_t)m * a.ldx + kk, lds + off_x + m * xrow + u * 1024);
+      }
+    if (a.norm >= 0) {
+      const int Ug = (K + 511) >> 9;
+      for (int u = wave; u < Ug; u += MG_WAVES) {
+        const int kk = u * 512 + lane * 8;
+        if (kk < K) {
+          dma16((const uint16_t*)G.ng + kk, lds + MG_LDS_G + u * 1024);
+          if (a.norm == 0 && G.nb) dma16((const uint16_t*)G.nb + kk, lds + off_b + u * 1024);
+        }
+      }
+    }
+  }
+
+  // ---- 2. bias and residual of the outputs this thread will finish (output e = tid + 512 i:
+  // row = e % R inside the tile, then the input row, then the tile ordinal)
+  constexpr int R = PAIRED ? 8 : 16;
+  const int nout = ntiles * M * R;
+  auto out_coord = [&](int e, int& ord, int& col, int& row, int& n) {
+    row = e & (R - 1);
+    const int f = e / R;
+    ord = f / M; col = f - ord * M;
+    n = ((int)blockIdx.x + ord * grid) * R + row;
+  };
+  // (the bf16 bias values stay raw until the epilogue: converting them here would wait for the loads)
+  const uint16_t* const B0 = (const uint16_t*)G.B[0];
+  const uint16_t* const B1 = (const uint16_t*)G.B[1];
+  const uint16_t* const B2 = (const uint16_t*)G.B[2];
+  auto out_operands = [&](int col, int n, uint32_t& b0, uint32_t& b1, float& rsd) {
+    b0 = 0u; b1 = 0u; rsd = 0.f;
+    if (PAIRED) {
+      if (B0) b0 = B0[n];
+      if (B1) b1 = B1[n];
+    } else if (B0) {      // a model has either all linear biases or none
+      int seg = 0, loc = n;
+      if (loc >= a.N[0]) { loc -= a.N[0]; seg = 1; if (loc >= a.N[1]) { loc -= a.N[1]; seg = 2; } }
+      const uint16_t* bp = seg == 0 ? B0 : (seg == 1 ? B1 : B2);
+      b0 = bp[loc];
+    }
+    if (G.Rsd) rsd = G.Rsd[(size_t)col * a.ldy + n];
+  };
+  uint32_t p_b0[MG_EP], p_b1[MG_EP]; float p_rsd[MG_EP];
+#pragma unroll
+  for (int i = 0; i < MG_EP; ++i) {
+    p_b0[i] = 0u; p_b1[i] = 0u; p_rsd[i] = 0.f;
+    const int e = tid + i * MG_THREADS;
+    if (e < nout) {
+      int ord, col, row, n; out_coord(e, ord, col, row, n);
+      if (n < a.ntot) out_operands(col, n, p_b0[i], p_b1[i], p_rsd[i]);
+    }
+  }
+
+  // ---- 3. the weight stream: wave w owns k-blocks [kb0, kb0 + nblk) of every tile blockIdx.x,
+  // + gridDim.x, ...; MG_BATCH blocks per batch, MG_RING batches in flight.  Every batch is always
+  // requested in full: slots past the wave's share (or past the last tile) re-read the start of the
+  // matrix, which is in the cache by then, and are never used.
+  const int nb8 = (KT + MG_WAVES - 1) / MG_WAVES;
+  const int kb0 = wave * nb8 < KT ? wave * nb8 : KT;
+  const int nblk = (kb0 + nb8 < KT ? kb0 + nb8 : KT) - kb0;
+  const int NBT = (nb8 + MG_BATCH - 1) / MG_BATCH;           // batches per tile, the same for every wave
+  const int Q = ntiles * NBT;
+  const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void*)G.P, 0, (int)a.wbytes, 0x00020000);
+  const unsigned lane16 = lane * 16;
+  int l_tile = 0, l_b = 0;     // tile ordinal and batch inside the tile of the next request
+  auto issue = [&](u32x4 (&buf)[MG_BATCH]) {
+    const bool live = l_tile < ntiles;
+    const unsigned base = (unsigned)(((int)blockIdx.x + l_tile * grid) * KT + kb0 + l_b * MG_BATCH) * 1024u;
+#pragma unroll
+    for (int j = 0; j < MG_BATCH; ++j) {
+      const bool ok = live && l_b * MG_BATCH + j < nblk;
+      buf[j] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, ok ? base + j * 1024u : 0u, 2);   // 2: non-temporal
+    }
+    if (++l_b == NBT) { l_b = 0; ++l_tile; }
+  };
+  u32x4 ring[MG_RING][MG_BATCH];
+#pragma unroll
+  for (int r = 0; r < MG_RING; ++r) issue(ring[r]);
+
+  // ---- 4. norm statistics and the split into two bf16 terms, in place: the 32 bytes that held the
+  // floats k .. k+7 (k a multiple of 8) then hold hi(k..k+7) | lo(k..k+7).  One fixed order per row:
+  // thread t sums the 8-element chunks t, t + 512, ... in turn, butterfly inside each wave, the eight
+  // wave sums in index order.  LayerNorm: mean first, then the squared deviations.
+  // everything requested before the weight stream has arrived once only the MG_RING * MG_BATCH newest
+  // loads are outstanding; then the workgroup's rows are complete in LDS
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(MG_RING * MG_BATCH) : "memory");
+  const int nchunk = KT * 4;                  // 32-byte chunks (8 elements) per staged row
+  auto combine8 = [&](const float* r) { return ((((((r[0] + r[1]) + r[2]) + r[3]) + r[4]) + r[5]) + r[6]) + r[7]; };
+  if (a.norm >= 0) {
+    if (a.norm == 0) {
+      for (int m = 0; m < M; ++m) {
+        float sm = 0.f;
+        for (int c = tid; c * 8 < K; c += MG_THREADS) {
+          const float4* px = (const float4*)(lds + off_x + m * xrow + c * 32);
+          const float4 v = px[0], w = px[1];
+          sm += v.x; sm += v.y; sm += v.z; sm += v.w; sm += w.x; sm += w.y; sm += w.z; sm += w.w;
+        }
+        sm = wave_sum(sm);
+        if (lane == 0) redA[m * MG_WAVES + wave] = sm;
+      }
+      __syncthreads();
+    }
+    for (int m = 0; m < M; ++m) {
+      const float mu = a.norm == 0 ? combine8(redA + m * MG_WAVES) / (float)K : 0.f;
+      float s2 = 0.f;
+      for (int c = tid; c * 8 < K; c += MG_THREADS) {
+        const float4* px = (const float4*)(lds + off_x + m * xrow + c * 32);
+        const float4 v = px[0], w = px[1];
+        const float d[8] = {v.x - mu, v.y - mu, v.z - mu, v.w - mu, w.x - mu, w.y - mu, w.z - mu, w.w - mu};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s2 = fmaf(d[e], d[e], s2);
+      }
+      s2 = wave_sum(s2);
+      if (lane == 0) redB[m * MG_WAVES + wave] = s2;
+    }
+    __syncthreads();
+    if (tid < M) {
+      stat[tid] = a.norm == 0 ? combine8(redA + tid * MG_WAVES) / (float)K : 0.f;
+      stat[16 + tid] = 1.0f / sqrtf(combine8(redB + tid * MG_WAVES) / (float)K + a.eps);
+    }
+    __syncthreads();
+  }
+  for (int m = 0; m < M; ++m) {
+    const float mu = a.norm >= 0 ? stat[m] : 0.f, rs = a.norm >= 0 ? stat[16 + m] : 1.f;
+    for (int c = tid; c < nchunk; c += MG_THREADS) {
+      char* px = lds + off_x + m * xrow + c * 32;
+      float xv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (c * 8 < K) {
+        const float4 v = ((const float4*)px)[0], w = ((const float4*)px)[1];
+        xv[0] = v.x; xv[1] = v.y; xv[2] = v.z; xv[3] = v.w; xv[4] = w.x; xv[5] = w.y; xv[6] = w.z; xv[7] = w.w;
+        if (a.norm >= 0) {
+          const u32x4 gq = *(const u32x4*)(lds + MG_LDS_G + c * 16);
+          float gf[8]; WTr<bf16_t>::unpack(gq, gf);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) xv[e] = (xv[e] - mu) * rs * gf[e];
+          if (a.norm == 0 && G.nb) {
+            const u32x4 bq = *(const u32x4*)(lds + off_b + c * 16);
+            float bf[8]; WTr<bf16_t>::unpack(bq, bf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xv[e] += bf[e];
+          }
+        }
+      }
+      uint32_t hi[8], lo[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        hi[e] = f32_to_bf16(xv[e]);
+        lo[e] = f32_to_bf16(xv[e] - bf16_to_f32((uint16_t)hi[e]));
+      }
+      ((uint4*)px)[0] = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+      ((uint4*)px)[1] = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+    }
+  }
+  __syncthreads();
+
+  // ---- 5. main loop.  B operand: lane l feeds column l % 16 (input row; lanes past M read row 0 and
+  // their columns are never stored) and the eight k of chunk l / 16.
+  const int bm = lane & 15, bc = lane >> 4;
+  const char* xlane = lds + off_x + (bm < M ? bm : 0) * xrow + bc * 32 + kb0 * 128;
+  float* plane = (float*)(lds + off_part) + (wave * M + bm) * 16 + bc * 4;   // + ord * 8 * M * 16
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  int c_ord = 0, c_b = 0;
+  auto consume = [&](u32x4 (&cur)[MG_BATCH]) {
+#pragma unroll
+    for (int j = 0; j < MG_BATCH; ++j) {
+      const int s = c_b * MG_BATCH + j;
+      if (s < nblk) {                      // the same for the whole wave
+        const u32x4* xp = (const u32x4*)(xlane + s * 128);
+        const u32x4 bh = xp[0], bl = xp[1];
+        const bf16x8 av = __builtin_bit_cast(bf16x8, cur[j]);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl), acc, 0, 0, 0);
+      }
+    }
+    if (++c_b == NBT) {
+      // this wave's partial sums of the tile: lane l holds rows 4 (l / 16) .. + 3 of column l % 16
+      if (bm < M) *(f32x4*)(plane + c_ord * (MG_WAVES * 16) * M) = acc;
+      acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+      c_b = 0; ++c_ord;
+    }
+  };
+  for (int q = 0; q < Q; q += MG_RING) {
+#pragma unroll
+    for (int r = 0; r < MG_RING; ++r) {
+      if (q + r < Q) consume(ring[r]);
+      issue(ring[r]);
+    }
+  }
+  __syncthreads();
+
+  // ---- 6. epilogue: the eight partials of an output in wave order, bias, activation, residual
+  auto finish = [&](int e, uint32_t rb0, uint32_t rb1, float rsd) {
+    int ord, col, row, n; out_coord(e, ord, col, row, n);
+    if (n >= a.ntot) return;
+    const float b0 = __uint_as_float(rb0 << 16), b1 = __uint_as_float(rb1 << 16);
+    const float* pp = (const float*)(lds + off_part) + (ord * MG_WAVES * M + col) * 16 + row;
+    const int ws = M * 16;
+    float s = pp[0];
+#pragma unroll
+    for (int w = 1; w < MG_WAVES; ++w) s += pp[w * ws];
+    float y;
+    if (PAIRED) {
+      float u = pp[8];
+#pragma unroll
+      for (int w = 1; w < MG_WAVES; ++w) u += pp[w * ws + 8];
+      y = silu(s + b0) * (u + b1);
+    } else {
+      y = s + b0;
+      if (a.act == 1) y = gelu_erf(y);
+      else if (a.act == 2) y = fmaxf(y, 0.f);
+    }
+    y += rsd;
+    G.Y[(size_t)col * a.ldy + n] = y;
+    if (a.topk > 0 && col == 0) hlog[ord * 16 + row] = y;
+  };
+#pragma unroll
+  for (int i = 0; i < MG_EP; ++i) {
+    const int e = tid + i * MG_THREADS;
+    if (e < nout) finish(e, p_b0[i], p_b1[i], p_rsd[i]);
+  }
+  for (int e = tid + MG_EP * MG_THREADS; e < nout; e += MG_THREADS) {
+    int ord, col, row, n; out_coord(e, ord, col, row, n);
+    uint32_t b0 = 0u, b1 = 0u; float rsd = 0.f;
+    if (n < a.ntot) out_operands(col, n, b0, b1, rsd);
+    finish(e, b0, b1, rsd);
+  }
+
+  // ---- LM head: this workgroup's top-k by (logit descending, id ascending)
+  if (a.topk > 0) {
+    __syncthreads();
+    if (wave == 0) {
+      constexpr int EPL = HEAD_MAX_ROWS / WAVE;
+      float ev[EPL]; int ei[EPL];
+#pragma unroll
+      for (int u = 0; u < EPL; ++u) {
+        const int e = lane + u * WAVE;       // entry e = tile ordinal * 16 + row
+        ev[u] = -INFINITY; ei[u] = 0x7fffffff;
+        const int id = ((int)blockIdx.x + (e >> 4) * grid) * 16 + (e & 15);
+        if ((e >> 4) < ntiles && id < a.ntot) { ev[u] = hlog[e]; ei[u] = id; }
+      }
+      for (int r = 0; r < a.topk; ++r) {
+        float v = -INFINITY; int i = 0x7fffffff;
+#pragma unroll
+        for (int u = 0; u < EPL; ++u) if (better(ev[u], ei[u], v, i)) { v = ev[u]; i = ei[u]; }
+        wave_best(v, i);
+#pragma unroll
+        for (int u = 0; u < EPL; ++u) if (ei[u] == i) { ev[u] = -INFINITY; ei[u] = 0x7fffffff; }
+        if (lane == 0) { a.pk_val[blockIdx.x * MAXM + r] = v; a.pk_idx[blockIdx.x * MAXM + r] = i; }
+      }
+    }
+  }
+}
+
+}  // namespace ppd
