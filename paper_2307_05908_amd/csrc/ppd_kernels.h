@@ -33,7 +33,7 @@ constexpr int GEMM_LDS_HDR = 80;    // floats in front of the x tile: norm stati
 constexpr int HEAD_MAX_ROWS = 256;  // logits one workgroup of the head GEMM may produce (block top-k buffer)
 constexpr int ATT_THREADS = 256;
 constexpr int ATT_WAVES = ATT_THREADS / WAVE;
-constexpr int ATT_CHUNK = 128;      // positions per workgroup; chunk c covers [c*128, (c+1)*128)
+constexpr int ATT_CHUNK = 64;       // positions per workgroup; chunk c covers [c*64, (c+1)*64)
 constexpr int MAXM = 8;
 
 // Round state in device memory, written by the tiny state kernel before a round and by the
@@ -540,8 +540,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs a) {
 // row has its own key/value for position p, which this kernel also rotates
 // (RoPE), rounds to the cache type and stores: at cache slot p for the main
 // token, in the row's tail slot for a candidate.  A workgroup takes one head
-// and one chunk of 128 positions; all its cached keys and values are
-// requested before anything else is done.
+// and one chunk of 64 positions.  Request order (a wave's loads return in
+// order): the rows' own q, k, v and the rotation table first, then all cached
+// keys of the chunk, then all its values; the rotation runs while the keys are
+// on their way and the scores while the values are.
 struct AttnGroup {
   const float* qkv;     // [M][3*d_model]: q | k | v as produced by the QKV projection
   const void* Kc; const void* Vc;   // this layer's cache, [H][max_ctx][hd]
@@ -576,20 +578,39 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const AttnGroup& G,
   const bool owns_p = (p < j0 + ATT_CHUNK);
   const int cs = lane % LPR, rs = lane / LPR;
 
-  // request the chunk's cached keys and values
+  // own q, k, v of every row (element idx = tid + 256 u: row idx / HD, component idx % HD), with the
+  // rotation partner and the (cos, sin) pair
+  constexpr int NOWN = (MT * HD + ATT_THREADS - 1) / ATT_THREADS;
+  constexpr int half = HD / 2;
+  float oq[NOWN], ok_[NOWN], ov[NOWN], oqp[NOWN], okp[NOWN]; float2 ocz[NOWN];
+#pragma unroll
+  for (int u = 0; u < NOWN; ++u) {
+    const int idx = tid + u * ATT_THREADS;
+    const int m = idx / HD, i = idx - m * HD;
+    oq[u] = 0.f; ok_[u] = 0.f; ov[u] = 0.f; oqp[u] = 0.f; okp[u] = 0.f; ocz[u] = make_float2(1.f, 0.f);
+    if (m < M) {
+      const float* row = G.qkv + (size_t)m * 3 * a.d_model + (size_t)h * HD;
+      oq[u] = row[i]; ok_[u] = row[a.d_model + i]; ov[u] = row[2 * a.d_model + i];
+      if (a.rope) {
+        const int ip = i < half ? i + half : i - half;
+        ocz[u] = a.rope[(size_t)p * half + (i < half ? i : i - half)];
+        oqp[u] = row[ip]; okp[u] = row[a.d_model + ip];
+      }
+    }
+  }
+  // the chunk's cached keys, then its values; rows past the prefix re-read row 0 and are masked below
   const char* Kh = (const char*)G.Kc + (size_t)h * a.max_ctx * HD * sizeof(WT);
   const char* Vh = (const char*)G.Vc + (size_t)h * a.max_ctx * HD * sizeof(WT);
   u32x4 kreg[NP], vreg[NP];
 #pragma unroll
   for (int t = 0; t < NP; ++t) {
-    int j = j0 + t * RPP + wave * RPW + rs;
-    if (j < p) {
-      kreg[t] = ld_stream(Kh + ((size_t)j * HD + cs * VEC) * sizeof(WT));
-      vreg[t] = ld_stream(Vh + ((size_t)j * HD + cs * VEC) * sizeof(WT));
-    } else {
-      kreg[t] = (u32x4){0u, 0u, 0u, 0u};
-      vreg[t] = (u32x4){0u, 0u, 0u, 0u};
-    }
+    const int j = j0 + t * RPP + wave * RPW + rs;
+    kreg[t] = ld_stream(Kh + ((size_t)(j < p ? j : 0) * HD + cs * VEC) * sizeof(WT));
+  }
+#pragma unroll
+  for (int t = 0; t < NP; ++t) {
+    const int j = j0 + t * RPP + wave * RPW + rs;
+    vreg[t] = ld_stream(Vh + ((size_t)(j < p ? j : 0) * HD + cs * VEC) * sizeof(WT));
   }
 
   float* qs = lds;                    // [MT][HD]
@@ -599,27 +620,27 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const AttnGroup& G,
   float* st = sc + MT * ATT_CHUNK;    // [MT][2] max, sum
   float* ored = st + MT * 2;          // [ATT_WAVES][MT][HD]
 
-  // own q, k, v of every row: rotate, scale / round, store
-  for (int idx = tid; idx < M * HD; idx += ATT_THREADS) {
-    int m = idx / HD, i = idx - m * HD;
-    const float* row = G.qkv + (size_t)m * 3 * a.d_model + (size_t)h * HD;
-    float q = row[i], k = row[a.d_model + i], v = row[2 * a.d_model + i];
-    if (a.rope) {
-      constexpr int half = HD / 2;
-      int ii = i < half ? i : i - half;
-      float2 cz = a.rope[(size_t)p * half + ii];
-      float qo = i < half ? row[i + half] : row[i - half];
-      float kk = i < half ? row[a.d_model + i + half] : row[a.d_model + i - half];
-      if (i < half) { q = fmaf(q, cz.x, -(qo * cz.y)); k = fmaf(k, cz.x, -(kk * cz.y)); }
-      else          { q = fmaf(q, cz.x, qo * cz.y);    k = fmaf(k, cz.x, kk * cz.y); }
-    }
-    qs[m * HD + i] = q * a.scale;
-    ko[m * HD + i] = WTr<WT>::round(k);
-    vo[m * HD + i] = WTr<WT>::round(v);
-    if (owns_p) {
-      size_t d = (size_t)m * G.own_row_stride + (size_t)h * G.own_head_stride + i + (G.own_cache ? (size_t)p * HD : 0);
-      WTr<WT>::store1(G.ownK, d, k);
-      WTr<WT>::store1(G.ownV, d, v);
+  // rotate, scale / round, store the rows' own key and value
+#pragma unroll
+  for (int u = 0; u < NOWN; ++u) {
+    const int idx = tid + u * ATT_THREADS;
+    const int m = idx / HD, i = idx - m * HD;
+    if (m < M) {
+      float q = oq[u], k = ok_[u];
+      const float v = ov[u];
+      if (a.rope) {
+        const float2 cz = ocz[u];
+        if (i < half) { q = fmaf(q, cz.x, -(oqp[u] * cz.y)); k = fmaf(k, cz.x, -(okp[u] * cz.y)); }
+        else          { q = fmaf(q, cz.x, oqp[u] * cz.y);    k = fmaf(k, cz.x, okp[u] * cz.y); }
+      }
+      qs[m * HD + i] = q * a.scale;
+      ko[m * HD + i] = WTr<WT>::round(k);
+      vo[m * HD + i] = WTr<WT>::round(v);
+      if (owns_p) {
+        size_t d = (size_t)m * G.own_row_stride + (size_t)h * G.own_head_stride + i + (G.own_cache ? (size_t)p * HD : 0);
+        WTr<WT>::store1(G.ownK, d, k);
+        WTr<WT>::store1(G.ownV, d, v);
+      }
     }
   }
   __syncthreads();
@@ -681,6 +702,8 @@ __device__ __forceinline__ void attn_body(const AttnArgs& a, const AttnGroup& G,
     bool valid = j < j1;
     float vf[VEC];
     WTr<WT>::unpack(vreg[t], vf);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) vf[e] = valid ? vf[e] : 0.f;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       if (m >= M) continue;
@@ -749,14 +772,31 @@ __global__ void attn_merge_kernel(MergeArgs a) {
   int i = threadIdx.x;
   if (i >= a.HD) return;
   const float* base = a.part[g] + (((size_t)m * a.H + h) * a.nchunk_max) * (a.HD + 2);
+  const size_t cs = a.HD + 2;
+  constexpr int UB = 8;     // chunks whose loads are in flight together
   float mx = -INFINITY;
-  for (int c = 0; c < nc; ++c) mx = fmaxf(mx, base[(size_t)c * (a.HD + 2) + a.HD]);
+  for (int c0 = 0; c0 < nc; c0 += UB) {
+    float t[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) t[u] = base[(size_t)(c0 + u < nc ? c0 + u : c0) * cs + a.HD];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) mx = fmaxf(mx, t[u]);
+  }
   float o = 0.f, l = 0.f;
-  for (int c = 0; c < nc; ++c) {
-    const float* pc = base + (size_t)c * (a.HD + 2);
-    float w = expf(pc[a.HD] - mx);
-    o = fmaf(w, pc[i], o);
-    l = fmaf(w, pc[a.HD + 1], l);
+  for (int c0 = 0; c0 < nc; c0 += UB) {
+    float tm[UB], ts[UB], to[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const float* pc = base + (size_t)(c0 + u < nc ? c0 + u : c0) * cs;
+      tm[u] = pc[a.HD]; ts[u] = pc[a.HD + 1]; to[u] = pc[i];
+    }
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+      if (c0 + u < nc) {
+        float w = expf(tm[u] - mx);
+        o = fmaf(w, to[u], o);
+        l = fmaf(w, ts[u], l);
+      }
   }
   a.out[g][(size_t)m * a.d_model + (size_t)h * a.HD + i] = o / l;
 }
@@ -902,6 +942,8 @@ namespace ppd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int MG_THREADS = 512;     // 8 waves: each takes one eighth of the reduction length of a 16-row tile
 constexpr int MG_WAVES = MG_THREADS / WAVE;
@@ -1086,17 +1128,19 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
     }
     if (++l_b == NBT) { l_b = 0; ++l_tile; }
   };
+  // One batch per wave is what a compute unit keeps in flight: it goes out now, the rest of the ring
+  // after the rows are staged (a wave that asked for more would sit in the request queue instead of
+  // working on the rows).
   u32x4 ring[MG_RING][MG_BATCH];
-#pragma unroll
-  for (int r = 0; r < MG_RING; ++r) issue(ring[r]);
+  issue(ring[0]);
 
   // ---- 4. norm statistics and the split into two bf16 terms, in place: the 32 bytes that held the
   // floats k .. k+7 (k a multiple of 8) then hold hi(k..k+7) | lo(k..k+7).  One fixed order per row:
   // thread t sums the 8-element chunks t, t + 512, ... in turn, butterfly inside each wave, the eight
   // wave sums in index order.  LayerNorm: mean first, then the squared deviations.
-  // everything requested before the weight stream has arrived once only the MG_RING * MG_BATCH newest
-  // loads are outstanding; then the workgroup's rows are complete in LDS
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(MG_RING * MG_BATCH) : "memory");
+  // everything requested before the weight stream has arrived once only the MG_BATCH newest loads
+  // are outstanding; then the workgroup's rows are complete in LDS
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(MG_BATCH) : "memory");
   const int nchunk = KT * 4;                  // 32-byte chunks (8 elements) per staged row
   auto combine8 = [&](const float* r) { return ((((((r[0] + r[1]) + r[2]) + r[3]) + r[4]) + r[5]) + r[6]) + r[7]; };
   if (a.norm >= 0) {
@@ -1154,17 +1198,21 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
           }
         }
       }
-      uint32_t hi[8], lo[8];
+      // hi = bf16(x) (the hardware's round-to-nearest-even pair conversion), lo = bf16(x - hi)
+      uint32_t hp[4], lp[4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        hi[e] = f32_to_bf16(xv[e]);
-        lo[e] = f32_to_bf16(xv[e] - bf16_to_f32((uint16_t)hi[e]));
+      for (int e = 0; e < 4; ++e) {
+        hp[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){xv[2 * e], xv[2 * e + 1]}, bf16x2));
+        const float r0 = xv[2 * e] - __uint_as_float(hp[e] << 16), r1 = xv[2 * e + 1] - __uint_as_float(hp[e] & 0xffff0000u);
+        lp[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){r0, r1}, bf16x2));
       }
-      ((uint4*)px)[0] = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
-      ((uint4*)px)[1] = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+      ((uint4*)px)[0] = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+      ((uint4*)px)[1] = make_uint4(lp[0], lp[1], lp[2], lp[3]);
     }
   }
   __syncthreads();
+#pragma unroll
+  for (int r = 1; r < MG_RING; ++r) issue(ring[r]);
 
   // ---- 5. main loop.  B operand: lane l feeds column l % 16 (input row; lanes past M read row 0 and
   // their columns are never stored) and the eight k of chunk l / 16.
