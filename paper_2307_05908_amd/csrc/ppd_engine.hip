@@ -66,6 +66,7 @@ struct ppd_ctx {
   int graph_chunks[3];   // attention grid (128-position chunks) each graph was captured with
   int gmax1, gmax2, gmaxd; // workgroup budget of a GEMM launch: one group / per group of a two-group launch / per chain of the parallel phase
   int in_dual;           // launches belong to one of two concurrent chains
+  int skew;              // the candidates' chain starts half a layer after the main token's
   int nchunk_max;
   // round state
   int n_ctx;      // absolute position of the pending token x_t (-1: no prefill yet)
@@ -96,7 +97,8 @@ int g_create_hip_error = 0;   // hipError_t of the last ppd_create that failed w
     }                                           \
   } while (0)
 
-inline size_t cache_layer_bytes(const ppd_ctx* c) { return (size_t)c->d.max_ctx * c->d.d_model * c->kvbytes; }
+inline size_t cache_head_floats(const ppd_ctx* c) { return kv_blocks(c->d.max_ctx) * KV_BLOCK * c->d.head_dim; }
+inline size_t cache_layer_bytes(const ppd_ctx* c) { return (size_t)c->d.n_heads * cache_head_floats(c) * sizeof(float); }
 
 struct ProfScope {
   ppd_ctx* c; int cls; size_t idx; bool on; hipStream_t st = nullptr;
@@ -239,10 +241,10 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
 // itself reads the position from the device state and idle chunks return at once)
 hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups, int pmax) {
   dim3 grid(pmax / ATT_CHUNK + 1, a.H, ngroups);
-  int MB = ngroups == 2 ? a.g[1].M : 0;
-  const int MA = a.g[0].M;
-  if (c->d.head_dim == 64) return launch_attn_t<float, 64>(c->cur, a, MA, MB, grid);
-  return launch_attn_t<float, 128>(c->cur, a, MA, MB, grid);
+  int mmax = a.g[0].M;
+  if (ngroups == 2 && a.g[1].M > mmax) mmax = a.g[1].M;
+  if (c->d.head_dim == 64) return launch_attn_t<64>(c->cur, a, mmax, grid);
+  return launch_attn_t<128>(c->cur, a, mmax, grid);
 }
 
 // the same launch described for the MFMA kernel: P[g] = group g's repacked weights
@@ -273,12 +275,13 @@ struct RowGroup {
 
 // One transformer layer for one or two row groups (a pipelined step when two).
 // pmax: host-side upper bound of the rows' positions (sizes the attention grid only).
-int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
+int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages = 3) {
   const ppd_model_dims& d = c->d;
   const int dm = d.d_model, F = d.d_ff;
   const bool bias = d.has_bias != 0;
+  // stages: bit 0 = steps 1-2 (attention half), bit 1 = steps 3-5 (output projection and FFN)
   // 1. norm1 + QKV
-  {
+  if (stages & 1) {
     GemmArgs a; memset(&a, 0, sizeof a);
     for (int g = 0; g < ngroups; ++g) {
       const LayerW& w = c->L[rg[g].layer];
@@ -298,7 +301,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   // 2. RoPE + KV write + attention partials, then merge
-  {
+  if (stages & 1) {
     AttnArgs a; memset(&a, 0, sizeof a);
     MergeArgs mg; memset(&mg, 0, sizeof mg);
     const size_t part_row = (size_t)d.n_heads * c->nchunk_max * (d.head_dim + 2);
@@ -306,17 +309,11 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
       AttnGroup& G = a.g[g];
       const int l = rg[g].layer;
       G.qkv = c->qkv + (size_t)rg[g].row0 * 3 * dm;
-      G.Kc = c->Kc + (size_t)l * cache_layer_bytes(c);
-      G.Vc = c->Vc + (size_t)l * cache_layer_bytes(c);
-      if (rg[g].tail) {
-        size_t off = (size_t)l * c->k * dm * c->kvbytes;
-        G.ownK = c->tailK + off; G.ownV = c->tailV + off;
-        G.own_row_stride = dm; G.own_head_stride = d.head_dim; G.own_cache = 0;
-      } else {
-        size_t off = (size_t)l * cache_layer_bytes(c);
-        G.ownK = c->Kc + off; G.ownV = c->Vc + off;
-        G.own_row_stride = 0; G.own_head_stride = (long)d.max_ctx * d.head_dim; G.own_cache = 1;
-      }
+      G.Kc = (float*)(c->Kc + (size_t)l * cache_layer_bytes(c));
+      G.Vc = (float*)(c->Vc + (size_t)l * cache_layer_bytes(c));
+      G.tailK = (float*)c->tailK + (size_t)l * c->k * dm;
+      G.tailV = (float*)c->tailV + (size_t)l * c->k * dm;
+      G.own_cache = rg[g].tail ? 0 : 1;
       G.part = c->part + (size_t)rg[g].row0 * part_row;
       G.pos_off = rg[g].pos_off; G.M = rg[g].M;
       mg.part[g] = G.part; mg.out[g] = c->att + (size_t)rg[g].row0 * dm; mg.pos_off[g] = G.pos_off; mg.M[g] = G.M;
@@ -333,7 +330,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     HIPCHK(c, hipGetLastError());
   }
   // 3. output projection + residual
-  {
+  if (stages & 2) {
     GemmArgs a; memset(&a, 0, sizeof a);
     for (int g = 0; g < ngroups; ++g) {
       const LayerW& w = c->L[rg[g].layer];
@@ -350,7 +347,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   // 4. norm2 + FFN in (+ gate/up pairing) + activation
-  {
+  if (stages & 2) {
     GemmArgs a; memset(&a, 0, sizeof a);
     const bool swiglu = d.act == 2;
     for (int g = 0; g < ngroups; ++g) {
@@ -371,7 +368,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax) {
     HIPCHK(c, launch_gemm(c, a, ngroups, swiglu));
   }
   // 5. FFN out + residual
-  {
+  if (stages & 2) {
     GemmArgs a; memset(&a, 0, sizeof a);
     for (int g = 0; g < ngroups; ++g) {
       const LayerW& w = c->L[rg[g].layer];
@@ -442,8 +439,9 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     s.emb = embed_args(c, nullptr, c->k, 1, 1);
     grid = dim3((d.d_model + SEL_THREADS - 1) / SEL_THREADS, c->k);
   } else if (adopt) {
-    s.h = c->h; s.tailK = c->tailK; s.tailV = c->tailV; s.Kc = c->Kc; s.Vc = c->Vc;
-    s.nb = c->nb; s.H = d.n_heads; s.hd = d.head_dim; s.d_model = d.d_model; s.max_ctx = d.max_ctx; s.wbytes = c->kvbytes;
+    s.h = c->h; s.tailK = (const float*)c->tailK; s.tailV = (const float*)c->tailV; s.Kc = (float*)c->Kc; s.Vc = (float*)c->Vc;
+    s.head_floats = cache_head_floats(c);
+    s.nb = c->nb; s.H = d.n_heads; s.hd = d.head_dim; s.d_model = d.d_model; s.max_ctx = d.max_ctx;
     grid = dim3(c->nb, 2);
   }
   ProfScope ps(c, PPD_KC_SELECT);
@@ -485,12 +483,19 @@ int issue_round(ppd_ctx* c, int kind, int pmax) {
     // (kernel boundary, attention, staging of its input rows) the other keeps HBM busy
     ProfScope phase(c, PPD_KC_PHASE, 2);
     c->in_dual = 1;
+    // The candidates' chain starts half a layer behind the main token's, so that each chain's
+    // attention (little traffic, long waits) falls into the other's FFN matrices.
+    if (c->skew) {
+      RowGroup gm{dbar, 1, 0, 0, false};
+      c->cur = c->stream;
+      if ((rc = run_layer(c, 1, &gm, pmax, 1))) return rc;
+    }
     HIPCHK(c, hipEventRecord(c->fork_ev, c->stream));
     HIPCHK(c, hipStreamWaitEvent(c->stream2, c->fork_ev, 0));
     for (int j = 0; j < nb && !rc; ++j) {
       RowGroup gm{dbar + j, 1, 0, 0, false}, gb{j, k, 1, 1, true};
       c->cur = c->stream;
-      rc = run_layer(c, 1, &gm, pmax);
+      rc = run_layer(c, 1, &gm, pmax, (c->skew && j == 0) ? 2 : 3);
       c->cur = c->stream2;
       if (!rc) rc = run_layer(c, 1, &gb, pmax);
     }
@@ -633,6 +638,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   c->n_ctx = -1;
   c->use_graphs = env_int("PPD_GRAPHS", 1) != 2;      // PPD_GRAPHS=2 switches graph replay off
   c->dual = env_int("PPD_DUAL", 1) != 2;               // PPD_DUAL=2: two-group launches instead of two chains
+  c->skew = env_int("PPD_SKEW", 0) == 1;
   c->gmax1 = env_int("PPD_GMAX1", 512);
   c->gmaxd = env_int("PPD_GMAXD", 256);
   c->gmax2 = env_int("PPD_GMAX2", 256);
@@ -685,6 +691,9 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     e = hipMemcpy(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
   }
   if (e == hipSuccess) e = hipMemset(c->ds, 0, sizeof(DevState));
+  // the attention MFMAs read whole 16-position blocks: positions not yet written must hold finite numbers
+  if (e == hipSuccess) e = hipMemset(c->Kc, 0, (size_t)d.n_layers * cache_layer_bytes(c));
+  if (e == hipSuccess) e = hipMemset(c->Vc, 0, (size_t)d.n_layers * cache_layer_bytes(c));
   c->mfma = d.wdtype == 1 && env_int("PPD_MFMA", 1) != 2;
   if (e == hipSuccess && c->mfma) {
     // repack every linear weight into MFMA blocks (owned copies)

@@ -46,36 +46,20 @@ template hipError_t launch_gemm_t<float, false, 2>(hipStream_t, const GemmArgs&,
 template hipError_t launch_gemm_t<float, true, 2>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
 #endif
 #else
-template <typename WT, int HD>
-hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int MA, int MB, dim3 grid) {
-#define GO(ma, mb)                                                          \
-  do {                                                                      \
-    constexpr size_t lds_ = attn_lds_bytes<HD, (ma > mb ? ma : mb)>();      \
-    attn_kernel<WT, HD, ma, mb><<<grid, dim3(ATT_THREADS), lds_, stream>>>(a); \
-  } while (0)
-  if (MB == 0) {
-    switch (MA) {
-      case 1: GO(1, 0); break; case 2: GO(2, 0); break; case 3: GO(3, 0); break; case 4: GO(4, 0); break;
-      case 5: GO(5, 0); break; case 6: GO(6, 0); break; case 7: GO(7, 0); break; case 8: GO(8, 0); break;
-      default: return hipErrorInvalidValue;
-    }
-  } else {
-    if (MA != 1) return hipErrorInvalidValue;
-    switch (MB) {
-      case 1: GO(1, 1); break; case 2: GO(1, 2); break; case 3: GO(1, 3); break; case 4: GO(1, 4); break;
-      case 5: GO(1, 5); break; case 6: GO(1, 6); break; case 7: GO(1, 7); break; case 8: GO(1, 8); break;
-      default: return hipErrorInvalidValue;
-    }
-  }
-#undef GO
+// mmax: the largest row count of the launch's groups (sizes LDS)
+template <int HD>
+hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int mmax, dim3 grid) {
+  if (mmax < 1 || mmax > 16) return hipErrorInvalidValue;
+  const size_t lds = sizeof(float) * (size_t)attn_lds_floats<HD>(mmax);
+  if (lds > 64 * 1024) return hipErrorInvalidValue;     // the default dynamic LDS limit
+  attn_kernel<HD><<<grid, dim3(ATT_THREADS), lds, stream>>>(a);
   return hipGetLastError();
 }
 
-
 #if PPD_INST == 8
-template hipError_t launch_attn_t<float, 128>(hipStream_t, const AttnArgs&, int, int, dim3);
+template hipError_t launch_attn_t<128>(hipStream_t, const AttnArgs&, int, dim3);
 #elif PPD_INST == 9
-template hipError_t launch_attn_t<float, 64>(hipStream_t, const AttnArgs&, int, int, dim3);
+template hipError_t launch_attn_t<64>(hipStream_t, const AttnArgs&, int, dim3);
 #endif
 #endif
 

@@ -22,6 +22,7 @@ namespace ppd {
 
 struct bf16_t { uint16_t v; };
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int WAVE = 64;
 constexpr int GEMM_THREADS = 256;   // 4 waves
@@ -78,6 +79,14 @@ template <> struct WTr<bf16_t> {
 
 // weights and cached keys/values are read once per launch: stream them past the caches
 __device__ __forceinline__ u32x4 ld_stream(const void* p) { return __builtin_nontemporal_load((const u32x4*)p); }
+
+// 64 lanes x 16 bytes from per-lane global addresses to LDS at lds_dst + 16 * lane (lds_dst is the same
+// for the whole wave and goes through M0).  Written as assembly so that the wait for it stays ours:
+// the request counts in vmcnt like any load, and loads return in order.
+__device__ __forceinline__ void dma16(const void* src, void* lds_dst) {
+  const unsigned la = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst;
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(la) : "memory", "m0");
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -538,21 +547,41 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(GemmArgs a) {
 // [0, p) plus the row's own position p.  The rows of a group share p and the
 // cached prefix (the sub-processes all extend x_<=t by one candidate); each
 // row has its own key/value for position p, which this kernel also rotates
-// (RoPE), rounds to the cache type and stores: at cache slot p for the main
-// token, in the row's tail slot for a candidate.  A workgroup takes one head
-// and one chunk of 64 positions.  Request order (a wave's loads return in
-// order): the rows' own q, k, v and the rotation table first, then all cached
-// keys of the chunk, then all its values; the rotation runs while the keys are
-// on their way and the scores while the values are.
+// (RoPE) and stores: at cache position p for the main token, in the row's
+// tail slot for a candidate.
+//
+// Keys and values are cached in fp32, in blocks that are operands of
+// v_mfma_f32_16x16x4_f32 as they lie in memory.  A block holds 16 positions of
+// one head; inside it, for each group s of 16 components, 64 lanes x 4 floats:
+//   keys:   lane i + 16 c, float u = K[position i]        [component 16 s + 4 c + u]
+//   values: lane i + 16 c, float u = V[position 4 c + u]  [component 16 s + i]
+// so a wave reads one kilobyte per load, and one such register quadruple feeds
+// four MFMAs: scores = K q (rows: positions, columns: the group's token rows,
+// reduction over components) and outputs = V^T p (rows: components, reduction
+// over positions).  No shuffles, and up to 16 rows cost what one costs.
+//
+// A workgroup takes one head and one chunk of 64 positions, one block per
+// wave.  Request order (a wave's loads return in order): the rows' own q, k, v
+// (direct to LDS) and the rotation table first, then the block's keys, then
+// its values.
+constexpr int KV_BLOCK = 16;
+__host__ __device__ inline size_t kv_blocks(int max_ctx) { return (size_t)((max_ctx + ATT_CHUNK - 1) / ATT_CHUNK) * (ATT_CHUNK / KV_BLOCK); }
+// float index inside one head's cache
+__host__ __device__ inline size_t k_index(int pos, int comp, int HD) {
+  return (((size_t)(pos >> 4) * (HD / 16) + (comp >> 4)) * 64 + (pos & 15) + 16 * ((comp >> 2) & 3)) * 4 + (comp & 3);
+}
+__host__ __device__ inline size_t v_index(int pos, int comp, int HD) {
+  return (((size_t)(pos >> 4) * (HD / 16) + (comp >> 4)) * 64 + (comp & 15) + 16 * ((pos >> 2) & 3)) * 4 + (pos & 3);
+}
+
 struct AttnGroup {
   const float* qkv;     // [M][3*d_model]: q | k | v as produced by the QKV projection
-  const void* Kc; const void* Vc;   // this layer's cache, [H][max_ctx][hd]
-  void* ownK; void* ownV;           // destination of the rows' own key/value: the layer's cache (own_cache) or its tails
-  long own_row_stride, own_head_stride;   // in elements: dst = own + m*row + h*head + i  (+ p*hd when own_cache)
+  float* Kc; float* Vc; // this layer's cache: [H][blocks][HD/16][64][4]
+  float* tailK; float* tailV;   // own_cache == 0: destination of the rows' own key/value, [M][H][HD]
   float* part;          // [M][H][nchunk_max][hd+2] partial (unnormalised o, max, sum)
   int pos_off;          // the rows sit at position p = ds->pos + pos_off and attend to cached positions [0, p)
-  int own_cache;
-  int M;
+  int own_cache;        // the row's own key/value go to cache position p (one row only)
+  int M;                // rows, 1..16
 };
 struct AttnArgs {
   AttnGroup g[2];
@@ -562,199 +591,156 @@ struct AttnArgs {
   float scale;
 };
 
-template <typename WT, int HD, int MT>
-__device__ __forceinline__ void attn_body(const AttnArgs& a, const AttnGroup& G, float* lds) {
-  constexpr int VEC = WTr<WT>::VEC;
-  constexpr int LPR = HD / VEC;        // lanes per cached row
-  constexpr int RPW = WAVE / LPR;      // cached rows per wave per load
-  constexpr int RPP = RPW * ATT_WAVES; // rows per pass of the workgroup
-  constexpr int NP = ATT_CHUNK / RPP;  // passes per chunk
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <int HD> __host__ __device__ constexpr int attn_lds_floats(int M) {
+  // raw q|k|v, then q (scaled), own k, own v, scores, statistics (max, sum, own weight, -), wave partials
+  return M * (3 * HD + 3 * HD + ATT_CHUNK + 4 + ATT_WAVES * HD);
+}
+
+template <int HD>
+__global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
+  extern __shared__ float4 lds4[];
+  float* lds = (float*)lds4;
+  const AttnGroup& G = a.g[blockIdx.z];
+  constexpr int NS = HD / 16, half = HD / 2;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int h = blockIdx.y, c = blockIdx.x;
   const int p = a.ds->pos + G.pos_off, M = G.M;
   const int j0 = c * ATT_CHUNK;
   if (j0 > p) return;
-  const int j1 = (j0 + ATT_CHUNK < p + 1) ? j0 + ATT_CHUNK : p + 1;   // exclusive; position p is the row's own
   const bool owns_p = (p < j0 + ATT_CHUNK);
-  const int cs = lane % LPR, rs = lane / LPR;
+  float* raw = lds;                   // [M][3][HD]
+  float* qs = raw + M * 3 * HD;       // [M][HD]
+  float* ko = qs + M * HD;            // [M][HD]
+  float* vo = ko + M * HD;            // [M][HD]
+  float* sc = vo + M * HD;            // [M][ATT_CHUNK]
+  float* st = sc + M * ATT_CHUNK;     // [M][4]
+  float* ored = st + M * 4;           // [ATT_WAVES][M][HD]
 
-  // own q, k, v of every row (element idx = tid + 256 u: row idx / HD, component idx % HD), with the
-  // rotation partner and the (cos, sin) pair
-  constexpr int NOWN = (MT * HD + ATT_THREADS - 1) / ATT_THREADS;
-  constexpr int half = HD / 2;
-  float oq[NOWN], ok_[NOWN], ov[NOWN], oqp[NOWN], okp[NOWN]; float2 ocz[NOWN];
-#pragma unroll
-  for (int u = 0; u < NOWN; ++u) {
-    const int idx = tid + u * ATT_THREADS;
-    const int m = idx / HD, i = idx - m * HD;
-    oq[u] = 0.f; ok_[u] = 0.f; ov[u] = 0.f; oqp[u] = 0.f; okp[u] = 0.f; ocz[u] = make_float2(1.f, 0.f);
-    if (m < M) {
-      const float* row = G.qkv + (size_t)m * 3 * a.d_model + (size_t)h * HD;
-      oq[u] = row[i]; ok_[u] = row[a.d_model + i]; ov[u] = row[2 * a.d_model + i];
-      if (a.rope) {
-        const int ip = i < half ? i + half : i - half;
-        ocz[u] = a.rope[(size_t)p * half + (i < half ? i : i - half)];
-        oqp[u] = row[ip]; okp[u] = row[a.d_model + ip];
+  // own q, k, v of every row, as they are: kilobyte pieces of the [M][3][HD] image
+  {
+    const int nfl = M * 3 * HD;
+    for (int f0 = wave * 256; f0 < nfl; f0 += ATT_WAVES * 256) {
+      const int f = f0 + lane * 4;
+      if (f < nfl) {
+        const int m = f / (3 * HD), r = f - m * (3 * HD), sec = r / HD, i = r - sec * HD;
+        dma16(G.qkv + (size_t)m * 3 * a.d_model + (size_t)sec * a.d_model + (size_t)h * HD + i, raw + f0);
       }
     }
   }
-  // the chunk's cached keys, then its values; rows past the prefix re-read row 0 and are masked below
-  const char* Kh = (const char*)G.Kc + (size_t)h * a.max_ctx * HD * sizeof(WT);
-  const char* Vh = (const char*)G.Vc + (size_t)h * a.max_ctx * HD * sizeof(WT);
-  u32x4 kreg[NP], vreg[NP];
+  // rotation pair of this thread's component (the same for every row)
+  const int ci = tid % HD;
+  float2 cz = make_float2(1.f, 0.f);
+  if (a.rope) cz = a.rope[(size_t)p * half + (ci < half ? ci : ci - half)];
+  // this wave's block: keys, then values
+  const size_t hb = (size_t)h * kv_blocks(a.max_ctx) + (size_t)(c * (ATT_CHUNK / KV_BLOCK) + wave);
+  const char* kb = (const char*)G.Kc + hb * (NS * 1024) + lane * 16;
+  const char* vb = (const char*)G.Vc + hb * (NS * 1024) + lane * 16;
+  f32x4_t kreg[NS], vreg[NS];
 #pragma unroll
-  for (int t = 0; t < NP; ++t) {
-    const int j = j0 + t * RPP + wave * RPW + rs;
-    kreg[t] = ld_stream(Kh + ((size_t)(j < p ? j : 0) * HD + cs * VEC) * sizeof(WT));
-  }
+  for (int s = 0; s < NS; ++s) kreg[s] = __builtin_nontemporal_load((const f32x4_t*)(kb + s * 1024));
 #pragma unroll
-  for (int t = 0; t < NP; ++t) {
-    const int j = j0 + t * RPP + wave * RPW + rs;
-    vreg[t] = ld_stream(Vh + ((size_t)(j < p ? j : 0) * HD + cs * VEC) * sizeof(WT));
-  }
+  for (int s = 0; s < NS; ++s) vreg[s] = __builtin_nontemporal_load((const f32x4_t*)(vb + s * 1024));
 
-  float* qs = lds;                    // [MT][HD]
-  float* ko = qs + MT * HD;           // [MT][HD] own key, rounded to cache type
-  float* vo = ko + MT * HD;           // [MT][HD]
-  float* sc = vo + MT * HD;           // [MT][ATT_CHUNK]
-  float* st = sc + MT * ATT_CHUNK;    // [MT][2] max, sum
-  float* ored = st + MT * 2;          // [ATT_WAVES][MT][HD]
-
-  // rotate, scale / round, store the rows' own key and value
-#pragma unroll
-  for (int u = 0; u < NOWN; ++u) {
-    const int idx = tid + u * ATT_THREADS;
-    const int m = idx / HD, i = idx - m * HD;
-    if (m < M) {
-      float q = oq[u], k = ok_[u];
-      const float v = ov[u];
-      if (a.rope) {
-        const float2 cz = ocz[u];
-        if (i < half) { q = fmaf(q, cz.x, -(oqp[u] * cz.y)); k = fmaf(k, cz.x, -(okp[u] * cz.y)); }
-        else          { q = fmaf(q, cz.x, oqp[u] * cz.y);    k = fmaf(k, cz.x, okp[u] * cz.y); }
-      }
-      qs[m * HD + i] = q * a.scale;
-      ko[m * HD + i] = WTr<WT>::round(k);
-      vo[m * HD + i] = WTr<WT>::round(v);
-      if (owns_p) {
-        size_t d = (size_t)m * G.own_row_stride + (size_t)h * G.own_head_stride + i + (G.own_cache ? (size_t)p * HD : 0);
-        WTr<WT>::store1(G.ownK, d, k);
-        WTr<WT>::store1(G.ownV, d, v);
-      }
-    }
-  }
-  __syncthreads();
-
-  float qr[MT][VEC];
-#pragma unroll
-  for (int m = 0; m < MT; ++m)
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) qr[m][e] = (m < M) ? qs[m * HD + cs * VEC + e] : 0.f;
-
-  // scores
-#pragma unroll
-  for (int t = 0; t < NP; ++t) {
-    int j = j0 + t * RPP + wave * RPW + rs;
-    bool valid = j < j1;
-    float kf[VEC];
-    WTr<WT>::unpack(kreg[t], kf);
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-      float s = 0.f;
-      if (valid && j == p) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) s = fmaf(qr[m][e], ko[(m < M ? m : 0) * HD + cs * VEC + e], s);
-      } else {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) s = fmaf(qr[m][e], kf[e], s);
-      }
-#pragma unroll
-      for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, WAVE);
-      if (cs == 0 && valid && m < M) sc[m * ATT_CHUNK + (j - j0)] = s;
-    }
-  }
-  __syncthreads();
-  // chunk-local softmax numerators: one wave per row
-  const int nj = j1 - j0;
-  for (int m = wave; m < M; m += ATT_WAVES) {
-    float mx = -INFINITY;
-    for (int j = lane; j < nj; j += WAVE) mx = fmaxf(mx, sc[m * ATT_CHUNK + j]);
-    mx = wave_max(mx);
-    float sum = 0.f;
-    for (int j = lane; j < nj; j += WAVE) {
-      float e = expf(sc[m * ATT_CHUNK + j] - mx);
-      sc[m * ATT_CHUNK + j] = e;
-      sum += e;
-    }
-    sum = wave_sum(sum);
-    if (lane == 0) { st[m * 2] = mx; st[m * 2 + 1] = sum; }
-  }
-  __syncthreads();
-  // weighted values
-  float acc[MT][VEC];
-#pragma unroll
-  for (int m = 0; m < MT; ++m)
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[m][e] = 0.f;
-#pragma unroll
-  for (int t = 0; t < NP; ++t) {
-    int j = j0 + t * RPP + wave * RPW + rs;
-    bool valid = j < j1;
-    float vf[VEC];
-    WTr<WT>::unpack(vreg[t], vf);
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) vf[e] = valid ? vf[e] : 0.f;
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-      if (m >= M) continue;
-      float pj = valid ? sc[m * ATT_CHUNK + (j - j0)] : 0.f;
-      if (valid && j == p) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[m][e] = fmaf(pj, vo[m * HD + cs * VEC + e], acc[m][e]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[m][e] = fmaf(pj, vf[e], acc[m][e]);
-      }
-    }
-  }
-  // rows of the wave (lanes with equal cs), then the waves in index order
-#pragma unroll
-  for (int m = 0; m < MT; ++m)
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-      float v = acc[m][e];
-#pragma unroll
-      for (int o = 32; o >= LPR; o >>= 1) v += __shfl_xor(v, o, WAVE);
-      acc[m][e] = v;
-    }
-  if (rs == 0) {
-#pragma unroll
-    for (int m = 0; m < MT; ++m)
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-        if (m < M) ored[(wave * MT + m) * HD + cs * VEC + e] = acc[m][e];
-  }
-  __syncthreads();
+  // the rows' own loads have arrived once only the 2 NS block loads are outstanding
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * NS) : "memory");
+  // rotate, scale, store the rows' own key and value
   for (int idx = tid; idx < M * HD; idx += ATT_THREADS) {
-    int m = idx / HD, i = idx - m * HD;
-    float o = ored[(0 * MT + m) * HD + i];
+    const int m = idx / HD, i = idx - m * HD;     // i == ci: ATT_THREADS is a multiple of HD
+    const float* r = raw + m * 3 * HD;
+    float q = r[i], k = r[HD + i];
+    const float v = r[2 * HD + i];
+    if (a.rope) {
+      const int ip = i < half ? i + half : i - half;
+      const float qo = r[ip], kk = r[HD + ip];
+      if (i < half) { q = fmaf(q, cz.x, -(qo * cz.y)); k = fmaf(k, cz.x, -(kk * cz.y)); }
+      else          { q = fmaf(q, cz.x, qo * cz.y);    k = fmaf(k, cz.x, kk * cz.y); }
+    }
+    qs[m * HD + i] = q * a.scale;
+    ko[m * HD + i] = k;
+    vo[m * HD + i] = v;
+    if (owns_p) {
+      if (G.own_cache) {
+        const size_t base = (size_t)h * kv_blocks(a.max_ctx) * (KV_BLOCK * HD);
+        G.Kc[base + k_index(p, i, HD)] = k;
+        G.Vc[base + v_index(p, i, HD)] = v;
+      } else {
+        const size_t d = ((size_t)m * a.H + h) * HD + i;
+        G.tailK[d] = k;
+        G.tailV[d] = v;
+      }
+    }
+  }
+  __syncthreads();
+
+  // scores of the block's 16 positions: lane l = n + 16 c feeds column n (row n of the group; lanes
+  // past M repeat row 0, their columns are never read) and components 16 s + 4 c + u
+  const int bn = lane & 15, bc = lane >> 4;
+  const int bm = bn < M ? bn : 0;
+  {
+    f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int w = 1; w < ATT_WAVES; ++w) o += ored[(w * MT + m) * HD + i];
+    for (int s = 0; s < NS; ++s) {
+      const f32x4_t q4 = *(const f32x4_t*)(qs + bm * HD + 16 * s + 4 * bc);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sacc = __builtin_amdgcn_mfma_f32_16x16x4f32(kreg[s][u], q4[u], sacc, 0, 0, 0);
+    }
+    // sacc[jj]: position 16 wave + 4 bc + jj of the chunk, row bn.  Cached positions keep their score,
+    // later ones get -inf, the rows' own position is filled in below.
+    if (bn < M) {
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int jl = 16 * wave + 4 * bc + jj, j = j0 + jl;
+        if (j != p) sc[bn * ATT_CHUNK + jl] = j < p ? sacc[jj] : -INFINITY;
+      }
+    }
+  }
+  if (owns_p) {
+    for (int m = wave; m < M; m += ATT_WAVES) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < HD / WAVE; ++e) s = fmaf(qs[m * HD + lane + e * WAVE], ko[m * HD + lane + e * WAVE], s);
+      s = wave_sum(s);
+      if (lane == 0) sc[m * ATT_CHUNK + (p - j0)] = s;
+    }
+  }
+  __syncthreads();
+  // chunk-local softmax numerators: one wave per row, one position per lane
+  for (int m = wave; m < M; m += ATT_WAVES) {
+    const float v = sc[m * ATT_CHUNK + lane];
+    const float mx = wave_max(v);
+    const float e = expf(v - mx);
+    const float sum = wave_sum(e);
+    const bool own = owns_p && lane == p - j0;
+    sc[m * ATT_CHUNK + lane] = own ? 0.f : e;       // the own position is added outside the MFMAs
+    if (own) st[m * 4 + 2] = e;
+    if (lane == 0) { st[m * 4] = mx; st[m * 4 + 1] = sum; }
+  }
+  __syncthreads();
+  // weighted values of the block: rows = components 16 s + i, reduction over its 16 positions 4 c + u
+  {
+    const f32x4_t p4 = *(const f32x4_t*)(sc + bm * ATT_CHUNK + 16 * wave + 4 * bc);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      f32x4_t oacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) oacc = __builtin_amdgcn_mfma_f32_16x16x4f32(vreg[s][u], p4[u], oacc, 0, 0, 0);
+      // oacc[jj]: component 16 s + 4 bc + jj, row bn
+      if (bn < M) *(f32x4_t*)(ored + (wave * M + bn) * HD + 16 * s + 4 * bc) = oacc;
+    }
+  }
+  __syncthreads();
+  // the four blocks in wave order, then the rows' own position
+  for (int idx = tid; idx < M * HD; idx += ATT_THREADS) {
+    const int m = idx / HD, i = idx - m * HD;
+    float o = ored[(0 * M + m) * HD + i];
+#pragma unroll
+    for (int w = 1; w < ATT_WAVES; ++w) o += ored[(w * M + m) * HD + i];
+    if (owns_p) o = fmaf(st[m * 4 + 2], vo[m * HD + i], o);
     float* dst = G.part + (((size_t)m * a.H + h) * a.nchunk_max + c) * (HD + 2);
     dst[i] = o;
-    if (i == 0) { dst[HD] = st[m * 2]; dst[HD + 1] = st[m * 2 + 1]; }
+    if (i == 0) { dst[HD] = st[m * 4]; dst[HD + 1] = st[m * 4 + 1]; }
   }
-}
-
-template <typename WT, int HD, int MA, int MB>
-__global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
-  extern __shared__ float4 lds4[];
-  float* lds = (float*)lds4;
-  if (MB == 0 || blockIdx.z == 0) attn_body<WT, HD, MA>(a, a.g[0], lds);
-  else attn_body<WT, HD, (MB < 1 ? 1 : MB)>(a, a.g[1], lds);
-}
-template <int HD, int MT> constexpr size_t attn_lds_bytes() {
-  return sizeof(float) * (3 * MT * HD + MT * ATT_CHUNK + MT * 2 + ATT_WAVES * MT * HD);
 }
 
 // merge of the chunk partials, chunks in index order
@@ -773,16 +759,9 @@ __global__ void attn_merge_kernel(MergeArgs a) {
   if (i >= a.HD) return;
   const float* base = a.part[g] + (((size_t)m * a.H + h) * a.nchunk_max) * (a.HD + 2);
   const size_t cs = a.HD + 2;
-  constexpr int UB = 8;     // chunks whose loads are in flight together
-  float mx = -INFINITY;
-  for (int c0 = 0; c0 < nc; c0 += UB) {
-    float t[UB];
-#pragma unroll
-    for (int u = 0; u < UB; ++u) t[u] = base[(size_t)(c0 + u < nc ? c0 + u : c0) * cs + a.HD];
-#pragma unroll
-    for (int u = 0; u < UB; ++u) mx = fmaxf(mx, t[u]);
-  }
-  float o = 0.f, l = 0.f;
+  constexpr int UB = 16;    // chunks whose loads are in flight together
+  // running maximum over the batches; inside a batch every load is requested before anything is used
+  float mx = -INFINITY, o = 0.f, l = 0.f;
   for (int c0 = 0; c0 < nc; c0 += UB) {
     float tm[UB], ts[UB], to[UB];
 #pragma unroll
@@ -790,6 +769,11 @@ __global__ void attn_merge_kernel(MergeArgs a) {
       const float* pc = base + (size_t)(c0 + u < nc ? c0 + u : c0) * cs;
       tm[u] = pc[a.HD]; ts[u] = pc[a.HD + 1]; to[u] = pc[i];
     }
+    float bm = mx;
+#pragma unroll
+    for (int u = 0; u < UB; ++u) if (c0 + u < nc) bm = fmaxf(bm, tm[u]);
+    const float rescale = expf(mx - bm);     // 0 for the first batch (mx = -inf), 1 when the maximum stays
+    o *= rescale; l *= rescale; mx = bm;
 #pragma unroll
     for (int u = 0; u < UB; ++u)
       if (c0 + u < nc) {
@@ -820,9 +804,10 @@ struct SelectArgs {
   EmbedArgs emb;        // candidate rows (mode 0)
   // adoption (mode 1)
   float* h;                 // [1+k][d_model]: row 0 main, rows 1.. candidates
-  const void* tailK; const void* tailV;   // [nb][k][H][hd]
-  void* Kc; void* Vc;       // [L][H][max_ctx][hd]
-  int nb, H, hd, d_model, max_ctx, wbytes;
+  const float* tailK; const float* tailV;   // [nb][k][H][hd]
+  float* Kc; float* Vc;     // [L][H][blocks][hd/16][64][4]
+  size_t head_floats;       // floats of one head's cache
+  int nb, H, hd, d_model, max_ctx;
 };
 constexpr int SEL_THREADS = 256;
 
@@ -907,13 +892,13 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   const int pos_next = a.ds->pos + 1;
   if (l == 0 && blockIdx.y == 0)
     for (int i = tid; i < a.d_model; i += SEL_THREADS) a.h[i] = a.h[(size_t)(1 + midx) * a.d_model + i];
-  const char* src = (const char*)(blockIdx.y == 0 ? a.tailK : a.tailV) + ((size_t)l * a.k + midx) * a.d_model * a.wbytes;
-  char* dst = (char*)(blockIdx.y == 0 ? a.Kc : a.Vc) + (size_t)l * a.H * a.max_ctx * a.hd * a.wbytes;
-  const int row_bytes = a.hd * a.wbytes;   // multiple of 16
-  for (int idx = tid; idx < a.H * (row_bytes / 16); idx += SEL_THREADS) {
-    int hh = idx / (row_bytes / 16), q = idx - hh * (row_bytes / 16);
-    uint4 v = *(const uint4*)(src + (size_t)hh * row_bytes + q * 16);
-    *(uint4*)(dst + ((size_t)hh * a.max_ctx + pos_next) * row_bytes + q * 16) = v;
+  // tails are [nb][k][H][hd] rows; the cache is blocked (k_index / v_index)
+  const float* src = (blockIdx.y == 0 ? a.tailK : a.tailV) + ((size_t)l * a.k + midx) * a.d_model;
+  float* dst = (blockIdx.y == 0 ? a.Kc : a.Vc) + (size_t)l * a.H * a.head_floats;
+  for (int idx = tid; idx < a.H * a.hd; idx += SEL_THREADS) {
+    const int hh = idx / a.hd, i = idx - hh * a.hd;
+    const size_t o = (size_t)hh * a.head_floats + (blockIdx.y == 0 ? k_index(pos_next, i, a.hd) : v_index(pos_next, i, a.hd));
+    dst[o] = src[idx];
   }
 }
 
@@ -1020,14 +1005,6 @@ __host__ __device__ inline int mg_lds_layout(int K, int M, int norm, int tiles_w
   off_part = off_b + (norm == 0 ? gsz : 0);
   off_x = off_part + tiles_wg * MG_WAVES * M * 64;
   return off_x + M * xrow;
-}
-
-// 64 lanes x 16 bytes from per-lane global addresses to LDS at lds_dst + 16 * lane (lds_dst is the same
-// for the whole wave and goes through M0).  Written as assembly so that the wait for it stays ours:
-// the request counts in vmcnt like any load, and loads return in order.
-__device__ __forceinline__ void dma16(const void* src, void* lds_dst) {
-  const unsigned la = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst;
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(la) : "memory", "m0");
 }
 
 template <bool PAIRED>

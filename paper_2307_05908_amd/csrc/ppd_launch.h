@@ -8,7 +8,7 @@ namespace ppd {
 template <typename WT, bool PAIRED, int WR>
 hipError_t launch_gemm_t(hipStream_t stream, const GemmArgs& a, int MA, int MB, dim3 grid, size_t lds);
 
-template <typename WT, int HD>
-hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int MA, int MB, dim3 grid);
+template <int HD>
+hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int mmax, dim3 grid);
 
 }  // namespace ppd
