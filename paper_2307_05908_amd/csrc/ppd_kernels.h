@@ -88,15 +88,26 @@ __device__ __forceinline__ void dma16(const void* src, void* lds_dst) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(la) : "memory", "m0");
 }
 
+// Wave reductions on the data-parallel-primitive path: inside each row of 16 lanes with four
+// lane-permuting adds (partner lanes compute a + b and b + a, so all 16 agree), then the four row
+// results in row order.  Every lane returns the same value.
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_f32(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, WAVE);
-  return v;
+  v += dpp_f32<0xB1>(v);     // quad_perm [1,0,3,2]
+  v += dpp_f32<0x4E>(v);     // quad_perm [2,3,0,1]
+  v += dpp_f32<0x141>(v);    // row_half_mirror
+  v += dpp_f32<0x140>(v);    // row_mirror
+  return ((lane_f32(v, 0) + lane_f32(v, 16)) + lane_f32(v, 32)) + lane_f32(v, 48);
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
-  return v;
+  v = fmaxf(v, dpp_f32<0xB1>(v));
+  v = fmaxf(v, dpp_f32<0x4E>(v));
+  v = fmaxf(v, dpp_f32<0x141>(v));
+  v = fmaxf(v, dpp_f32<0x140>(v));
+  return fmaxf(fmaxf(lane_f32(v, 0), lane_f32(v, 16)), fmaxf(lane_f32(v, 32), lane_f32(v, 48)));
 }
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 // arg max by (value descending, id ascending) over a wave; every lane ends with the winner
@@ -659,17 +670,6 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
     qs[m * HD + i] = q * a.scale;
     ko[m * HD + i] = k;
     vo[m * HD + i] = v;
-    if (owns_p) {
-      if (G.own_cache) {
-        const size_t base = (size_t)h * kv_blocks(a.max_ctx) * (KV_BLOCK * HD);
-        G.Kc[base + k_index(p, i, HD)] = k;
-        G.Vc[base + v_index(p, i, HD)] = v;
-      } else {
-        const size_t d = ((size_t)m * a.H + h) * HD + i;
-        G.tailK[d] = k;
-        G.tailV[d] = v;
-      }
-    }
   }
   __syncthreads();
 
@@ -740,6 +740,18 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
     float* dst = G.part + (((size_t)m * a.H + h) * a.nchunk_max + c) * (HD + 2);
     dst[i] = o;
     if (i == 0) { dst[HD] = st[m * 4]; dst[HD + 1] = st[m * 4 + 1]; }
+    // the row's own key and value (stored last: no store waits in the request queue behind the block loads)
+    if (owns_p) {
+      if (G.own_cache) {
+        const size_t base = (size_t)h * kv_blocks(a.max_ctx) * (KV_BLOCK * HD);
+        G.Kc[base + k_index(p, i, HD)] = ko[m * HD + i];
+        G.Vc[base + v_index(p, i, HD)] = vo[m * HD + i];
+      } else {
+        const size_t d = ((size_t)m * a.H + h) * HD + i;
+        G.tailK[d] = ko[m * HD + i];
+        G.tailV[d] = vo[m * HD + i];
+      }
+    }
   }
 }
 
