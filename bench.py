@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # HBM bytes per launch of the roofline kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of
 # known size (profiles/llama7b_ppd_k3_kernels.txt); only valid for the configuration it was collected on
-MEASURED_TRAFFIC = {"llama7b": 181.09e6}
+MEASURED_TRAFFIC = {"llama7b": 180.80e6}
 
 
 def main():
@@ -126,7 +126,7 @@ def main():
     if dom:
         avg_s = dom["ms"] / dom["launches"] / 1e3
         ach = ffn_in_bytes / avg_s / 1e9
-        roof = {"bound": "hbm", "kernel": "gemm_kernel (norm + FFN-in matrices + activation), one row", "achieved": round(ach, 1),
+        roof = {"bound": "hbm", "kernel": "gemm_mfma_kernel<true> (norm + FFN-in gate and up matrices + SwiGLU), one row", "achieved": round(ach, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get(cfg.name) if cfg.name.startswith("llama7b") else None,
                 "bytes_per_launch": ffn_in_bytes, "avg_launch_us": round(avg_s * 1e6, 2)}

@@ -13,7 +13,7 @@ import tempfile
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libppd.so")
-N_INST = 10
+N_INST = 6
 DEPS = [os.path.join(CSRC, f) for f in ("ppd_engine.hip", "ppd_inst.hip", "ppd_kernels.h", "ppd_launch.h")] + \
        [os.path.join(os.path.dirname(HERE), "include", "ppd.h")]
 # -ffp-contract=off: every fused multiply-add in the kernels is an explicit fmaf, so a row's arithmetic

@@ -174,10 +174,7 @@ hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
     return paired ? launch_gemm_t<float, true, 2>(c->cur, a, MA, MB, grid, lds)
                   : launch_gemm_t<float, false, 2>(c->cur, a, MA, MB, grid, lds);
   }
-  if (wr == 4) return paired ? launch_gemm_t<bf16_t, true, 4>(c->cur, a, MA, MB, grid, lds)
-                             : launch_gemm_t<bf16_t, false, 4>(c->cur, a, MA, MB, grid, lds);
-  return paired ? launch_gemm_t<bf16_t, true, 2>(c->cur, a, MA, MB, grid, lds)
-                : launch_gemm_t<bf16_t, false, 2>(c->cur, a, MA, MB, grid, lds);
+  return hipErrorInvalidValue;   // bf16 weights never come here: they take the MFMA kernel
 }
 
 // ---- bf16 models: MFMA GEMM on repacked weights
@@ -694,7 +691,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   // the attention MFMAs read whole 16-position blocks: positions not yet written must hold finite numbers
   if (e == hipSuccess) e = hipMemset(c->Kc, 0, (size_t)d.n_layers * cache_layer_bytes(c));
   if (e == hipSuccess) e = hipMemset(c->Vc, 0, (size_t)d.n_layers * cache_layer_bytes(c));
-  c->mfma = d.wdtype == 1 && env_int("PPD_MFMA", 1) != 2;
+  c->mfma = d.wdtype == 1;
   if (e == hipSuccess && c->mfma) {
     // repack every linear weight into MFMA blocks (owned copies)
     auto repack = [&](const void* s0, const void* s1, const void* s2, int n0, int n1, int n2, int K, bool paired, void** out) {

@@ -3,7 +3,7 @@
 
 namespace ppd {
 
-#if PPD_INST < 8
+#if PPD_INST < 4
 // MA rows in group 0; MB rows in group 1 (0: single-group launch).  Launch shapes in use:
 // (1, 0) main token alone, (k, 0) the candidates alone, (1, k) both in one launch.
 template <typename WT, bool PAIRED, int WR>
@@ -28,21 +28,14 @@ hipError_t launch_gemm_t(hipStream_t stream, const GemmArgs& a, int MA, int MB, 
 }
 
 
+// (fp32 weights only: bf16 models run every GEMM on the MFMA kernel)
 #if PPD_INST == 0
-template hipError_t launch_gemm_t<bf16_t, false, 4>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
-#elif PPD_INST == 1
-template hipError_t launch_gemm_t<bf16_t, true, 4>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
-#elif PPD_INST == 2
-template hipError_t launch_gemm_t<bf16_t, false, 2>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
-#elif PPD_INST == 3
-template hipError_t launch_gemm_t<bf16_t, true, 2>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
-#elif PPD_INST == 4
 template hipError_t launch_gemm_t<float, false, 4>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
-#elif PPD_INST == 5
+#elif PPD_INST == 1
 template hipError_t launch_gemm_t<float, true, 4>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
-#elif PPD_INST == 6
+#elif PPD_INST == 2
 template hipError_t launch_gemm_t<float, false, 2>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
-#elif PPD_INST == 7
+#elif PPD_INST == 3
 template hipError_t launch_gemm_t<float, true, 2>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
 #endif
 #else
@@ -56,9 +49,9 @@ hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int mmax, dim3 g
   return hipGetLastError();
 }
 
-#if PPD_INST == 8
+#if PPD_INST == 4
 template hipError_t launch_attn_t<128>(hipStream_t, const AttnArgs&, int, dim3);
-#elif PPD_INST == 9
+#elif PPD_INST == 5
 template hipError_t launch_attn_t<64>(hipStream_t, const AttnArgs&, int, dim3);
 #endif
 #endif
