@@ -87,9 +87,27 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- PPD rounds
+    # ---- what a plain streaming read reaches on this GPU (1 GiB, the library's probe kernel)
+    probe_buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    probe_buf.zero_()
+    torch.cuda.synchronize()
+    stream_gbs = binding.ppd_stream_read_probe(probe_buf, iters=8)
+    del probe_buf
+
+    # ---- PPD rounds (each call is synchronous: the host clock around a call is the round's latency)
     P = binding.PPD(cfg, dev, k=k, exit_layer=e)
-    wall_ppd, _ = timed(P, lambda: P.ppd_step(want_info=False), W, K)
+    round_ms, round_hit = [], []
+
+    def ppd_round():
+        t = time.perf_counter()
+        _, info = P.ppd_step(want_info=True)
+        round_ms.append((time.perf_counter() - t) * 1e3)
+        round_hit.append(bool(info.matched))
+
+    wall_ppd, _ = timed(P, ppd_round, W, K)
+    round_ms, round_hit = np.array(round_ms[W:]), np.array(round_hit[W:])
+    # a round's length is set by how it starts: after a hit it resumes mid-stack (no solo phase when dbar = d/2)
+    after_hit = np.concatenate([[False], round_hit[:-1]])
     st = P.ppd_get_stats()
     ell = st["rounds"]
     p_hat = st["matches"] / ell
@@ -129,7 +147,8 @@ def main():
         roof = {"bound": "hbm", "kernel": "gemm_mfma_kernel<true> (norm + FFN-in gate and up matrices + SwiGLU), one row", "achieved": round(ach, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get(cfg.name) if cfg.name.startswith("llama7b") else None,
-                "bytes_per_launch": ffn_in_bytes, "avg_launch_us": round(avg_s * 1e6, 2)}
+                "bytes_per_launch": ffn_in_bytes, "avg_launch_us": round(avg_s * 1e6, 2),
+                "stream_read_GBps": round(stream_gbs, 1), "frac_of_stream_read": round(ach / stream_gbs, 4)}
     pp = ph.get("phase.g2")
     pipe = None
     if pp:
@@ -138,7 +157,8 @@ def main():
         step_bytes = 2 * wl + 2 * kv
         step_s = pp["ms"] / pp["launches"] / nb / 1e3
         pipe = {"bytes_per_step": step_bytes, "us_per_step": round(step_s * 1e6, 2),
-                "GBps": round(step_bytes / step_s / 1e9, 1), "hbm_frac": round(step_bytes / step_s / 1e9 / HBM_PEAK_GBS, 4)}
+                "GBps": round(step_bytes / step_s / 1e9, 1), "hbm_frac": round(step_bytes / step_s / 1e9 / HBM_PEAK_GBS, 4),
+                "frac_of_stream_read": round(step_bytes / step_s / 1e9 / stream_gbs, 4)}
     kernels = {n: {"avg_us": round(v["ms"] / v["launches"] * 1e3, 2), "launches": v["launches"]} for n, v in kt.items()}
 
     # ---- CPU oracle on the host cores (bounded sample)
@@ -166,6 +186,10 @@ def main():
         "config": {"workload": f"{cfg.name}: {d} layers, d_model {cfg.d_model}, d_ff {cfg.d_ff}, vocab {cfg.vocab}, "
                                f"batch 1, prompt {n_prompt} uniform-random ids, random-init N(0,0.02) weights",
                    "k": k, "exit_layer": e, "alpha": cfg.alpha},
+        "round_ms": {"mean": round(float(round_ms.mean()), 4), "p50": round(float(np.percentile(round_ms, 50)), 4),
+                     "p95": round(float(np.percentile(round_ms, 95)), 4),
+                     "after_hit_mean": round(float(round_ms[after_hit].mean()), 4) if after_hit.any() else None,
+                     "after_miss_mean": round(float(round_ms[~after_hit].mean()), 4) if (~after_hit).any() else None},
         "plain_greedy": {"tokens_per_s": round(K / wall_plain, 2), "ms_per_token": round(wall_plain / K * 1e3, 4)},
         "ppd_vs_plain_speed": round(wall_plain / wall_ppd, 4),
         "p_correct": round(p_hat, 4),

@@ -175,6 +175,12 @@ int ppd_set_profiling(ppd_ctx *ctx, int level);
 int ppd_set_graphs(ppd_ctx *ctx, int on);
 int ppd_get_kernel_time(ppd_ctx *ctx, int kernel_class, int groups, double *ms_total, uint64_t *launches);
 
+/* Measurement aid (not part of the method): read `bytes` of DEVICE memory at dev_buf `iters` times with a
+ * kernel that does nothing but non-temporal 16-byte loads (a few launch shapes, the best counts), and report the rate in GB/s (HOST
+ * output): the streaming rate this GPU reaches, next to which the decode kernels' rates are read.
+ * bytes must be a positive multiple of 16; the buffer is only read.  Runs on its own stream, synchronous. */
+int ppd_stream_read_probe(const void *dev_buf, uint64_t bytes, int iters, double *gbps);
+
 void ppd_destroy(ppd_ctx *ctx);
 
 const char *ppd_strerror(int code);

@@ -51,7 +51,7 @@ class Stats(ctypes.Structure):
 
 EXPORTS = ("ppd_create", "ppd_reset", "ppd_prefill", "ppd_step", "plain_greedy_step", "ppd_get_logits",
            "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_set_graphs", "ppd_get_kernel_time",
-           "ppd_destroy",
+           "ppd_stream_read_probe", "ppd_destroy",
            "ppd_strerror", "ppd_last_hip_error")
 
 _lib = None
@@ -81,6 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.ppd_set_profiling.argtypes = [vp, ci]
     lib.ppd_set_graphs.argtypes = [vp, ci]
     lib.ppd_get_kernel_time.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
+    lib.ppd_stream_read_probe.argtypes = [vp, ctypes.c_uint64, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_destroy.argtypes = [vp]
     lib.ppd_destroy.restype = None
     lib.ppd_strerror.argtypes = [ci]
@@ -113,6 +114,16 @@ def upload_model(model, device="cuda:0") -> Dict[str, object]:
     for f in _LAYER_FIELDS:
         dev[f] = [up(a) for a in model.layers[f]]
     return dev
+
+
+def ppd_stream_read_probe(dev_tensor, iters: int = 5) -> float:
+    """GB/s of a plain streaming read of a device tensor (measurement aid of the library)."""
+    nbytes = dev_tensor.numel() * dev_tensor.element_size()
+    out = ctypes.c_double(0.0)
+    rc = load_library().ppd_stream_read_probe(dev_tensor.data_ptr(), nbytes, iters, ctypes.byref(out))
+    if rc != 0:
+        raise PPDError(f"ppd_stream_read_probe: {load_library().ppd_strerror(rc).decode()}")
+    return float(out.value)
 
 
 class PPD:

@@ -872,6 +872,47 @@ int ppd_get_kernel_time(ppd_ctx* c, int kernel_class, int groups, double* ms_tot
   return PPD_OK;
 }
 
+int ppd_stream_read_probe(const void* dev_buf, uint64_t bytes, int iters, double* gbps) {
+  if (!dev_buf || !gbps || bytes == 0 || (bytes & 15) || iters < 1) return PPD_EINVAL;
+  hipStream_t st = nullptr; hipEvent_t e0 = nullptr, e1 = nullptr; uint32_t* sink = nullptr;
+  hipError_t e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e == hipSuccess) e = hipMalloc((void**)&sink, sizeof(uint32_t));
+  // the best of a few launch shapes (workgroups x loads in flight per thread): what the GPU can stream
+  double best = 0.0;
+  if (e == hipSuccess) {
+    const size_t n16 = bytes / 16;
+    const int grids[] = {1024, 2048, 4096, 8192};
+    for (int gi = 0; gi < 4 && e == hipSuccess; ++gi)
+      for (int u8 = 0; u8 < 2 && e == hipSuccess; ++u8) {
+        const dim3 grid(grids[gi]), block(256);
+        auto go = [&]() {
+          if (u8) hipLaunchKernelGGL(stream_read_kernel<8>, grid, block, 0, st, (const u32x4*)dev_buf, n16, sink);
+          else hipLaunchKernelGGL(stream_read_kernel<4>, grid, block, 0, st, (const u32x4*)dev_buf, n16, sink);
+        };
+        go();   // warm-up
+        e = hipEventRecord(e0, st);
+        for (int i = 0; i < iters && e == hipSuccess; ++i) { go(); e = hipGetLastError(); }
+        if (e == hipSuccess) e = hipEventRecord(e1, st);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e == hipSuccess && ms > 0.f) {
+          const double r = (double)bytes * iters / ((double)ms * 1e-3) / 1e9;
+          if (r > best) best = r;
+        }
+      }
+  }
+  if (sink) (void)hipFree(sink);
+  if (e1) (void)hipEventDestroy(e1);
+  if (e0) (void)hipEventDestroy(e0);
+  if (st) (void)hipStreamDestroy(st);
+  if (e != hipSuccess) { g_create_hip_error = (int)e; (void)hipGetLastError(); return PPD_EHIP; }
+  *gbps = best;
+  return PPD_OK;
+}
+
 void ppd_destroy(ppd_ctx* c) {
   if (!c) return;
   if (c->stream) (void)hipStreamSynchronize(c->stream);

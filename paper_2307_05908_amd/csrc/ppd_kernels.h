@@ -122,6 +122,22 @@ __device__ __forceinline__ void wave_best(float& v, int& i) {
 // ------------------------------------------------------------------ round state
 // (plain, non-template kernels are compiled into the engine's translation unit only)
 #ifdef PPD_ENGINE_TU
+// streaming-read probe: every thread walks the buffer with U 16-byte non-temporal loads in flight
+template <int U>
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* p, size_t n16, uint32_t* sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (; i + (U - 1) * stride < n16; i += U * stride) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = ld_stream(p + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc ^= v[u];
+  }
+  for (; i < n16; i += stride) acc ^= ld_stream(p + i);
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) *sink = acc.x;   // keeps the loads alive; practically never taken
+}
 __global__ void set_state_kernel(DevState* ds, int pos, int tok) {
   if (threadIdx.x == 0) { ds->pos = pos; if (tok >= 0) ds->next_tok = tok; }
 }

@@ -161,3 +161,13 @@ def test_edge_cases():
         got.append(tok)
     np.testing.assert_array_equal(got, otoks[:first + 1])
     assert Pe.plain_greedy_step() is None
+
+
+@pytest.mark.gpu
+def test_stream_read_probe_reports_a_plausible_rate():
+    """The library's measurement aid: 256 MiB read, between 1 and 8 TB/s on an MI355X."""
+    import torch
+    buf = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    rate = binding.ppd_stream_read_probe(buf, iters=4)
+    assert 1000.0 < rate < 8000.0, rate
