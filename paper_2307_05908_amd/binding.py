@@ -51,7 +51,7 @@ class Stats(ctypes.Structure):
 
 EXPORTS = ("ppd_create", "ppd_reset", "ppd_prefill", "ppd_step", "plain_greedy_step", "ppd_get_logits",
            "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_set_graphs", "ppd_get_kernel_time",
-           "ppd_stream_read_probe", "ppd_destroy",
+           "ppd_time_ffn_in", "ppd_stream_read_probe", "ppd_destroy",
            "ppd_strerror", "ppd_last_hip_error")
 
 _lib = None
@@ -81,6 +81,7 @@ def load_library() -> ctypes.CDLL:
     lib.ppd_set_profiling.argtypes = [vp, ci]
     lib.ppd_set_graphs.argtypes = [vp, ci]
     lib.ppd_get_kernel_time.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
+    lib.ppd_time_ffn_in.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_stream_read_probe.argtypes = [vp, ctypes.c_uint64, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_destroy.argtypes = [vp]
     lib.ppd_destroy.restype = None
@@ -214,6 +215,12 @@ class PPD:
 
     def ppd_set_graphs(self, on: bool):
         self._chk(load_library().ppd_set_graphs(self._h, int(on)), "ppd_set_graphs")
+
+    def ppd_time_ffn_in(self, reps: int = 64) -> float:
+        """Average milliseconds per FFN-in GEMM launch in a back-to-back burst (invalidates the sequence)."""
+        out = ctypes.c_double(0.0)
+        self._chk(load_library().ppd_time_ffn_in(self._h, reps, ctypes.byref(out)), "ppd_time_ffn_in")
+        return float(out.value)
 
     def ppd_get_kernel_time(self) -> Dict[str, Dict[str, float]]:
         out = {}

@@ -272,11 +272,11 @@ struct RowGroup {
 
 // One transformer layer for one or two row groups (a pipelined step when two).
 // pmax: host-side upper bound of the rows' positions (sizes the attention grid only).
-int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages = 3) {
+int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages = 15) {
   const ppd_model_dims& d = c->d;
   const int dm = d.d_model, F = d.d_ff;
   const bool bias = d.has_bias != 0;
-  // stages: bit 0 = steps 1-2 (attention half), bit 1 = steps 3-5 (output projection and FFN)
+  // stages: bit 0 = steps 1-2 (attention half), bit 1 = step 3, bit 2 = step 4, bit 3 = step 5
   // 1. norm1 + QKV
   if (stages & 1) {
     GemmArgs a; memset(&a, 0, sizeof a);
@@ -344,7 +344,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages 
     HIPCHK(c, launch_gemm(c, a, ngroups, false));
   }
   // 4. norm2 + FFN in (+ gate/up pairing) + activation
-  if (stages & 2) {
+  if (stages & 4) {
     GemmArgs a; memset(&a, 0, sizeof a);
     const bool swiglu = d.act == 2;
     for (int g = 0; g < ngroups; ++g) {
@@ -365,7 +365,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages 
     HIPCHK(c, launch_gemm(c, a, ngroups, swiglu));
   }
   // 5. FFN out + residual
-  if (stages & 2) {
+  if (stages & 8) {
     GemmArgs a; memset(&a, 0, sizeof a);
     for (int g = 0; g < ngroups; ++g) {
       const LayerW& w = c->L[rg[g].layer];
@@ -492,7 +492,7 @@ int issue_round(ppd_ctx* c, int kind, int pmax) {
     for (int j = 0; j < nb && !rc; ++j) {
       RowGroup gm{dbar + j, 1, 0, 0, false}, gb{j, k, 1, 1, true};
       c->cur = c->stream;
-      rc = run_layer(c, 1, &gm, pmax, (c->skew && j == 0) ? 2 : 3);
+      rc = run_layer(c, 1, &gm, pmax, (c->skew && j == 0) ? 14 : 15);
       c->cur = c->stream2;
       if (!rc) rc = run_layer(c, 1, &gb, pmax);
     }
@@ -869,6 +869,42 @@ int ppd_get_kernel_time(ppd_ctx* c, int kernel_class, int groups, double* ms_tot
     return PPD_EINVAL;
   *ms_total = c->kc_ms[kernel_class + (groups - 1) * PPD_KC_COUNT];
   *launches = c->kc_n[kernel_class + (groups - 1) * PPD_KC_COUNT];
+  return PPD_OK;
+}
+
+int ppd_time_ffn_in(ppd_ctx* c, int reps, double* ms_per_launch) {
+  if (!c || reps < 1 || !ms_per_launch) return PPD_EINVAL;
+  if (c->n_ctx < 0) return PPD_ESTATE;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  HIPCHK(c, hipEventCreate(&e0));
+  hipError_t e = hipEventCreate(&e1);
+  int rc = PPD_OK;
+  const int saved_prof = c->prof;
+  c->prof = 0;
+  c->cur = c->stream;
+  if (e == hipSuccess) {
+    // one untimed launch per distinct layer first would warm nothing that matters (the weights do not fit
+    // any cache); one warm-up launch for the code, then the timed burst
+    RowGroup g0{0, 1, 0, 0, false};
+    rc = run_layer(c, 1, &g0, 0, 4);
+    if (!rc) e = hipEventRecord(e0, c->stream);
+    for (int i = 0; i < reps && !rc && e == hipSuccess; ++i) {
+      RowGroup g{(1 + i) % c->d.n_layers, 1, 0, 0, false};
+      rc = run_layer(c, 1, &g, 0, 4);
+    }
+    if (!rc && e == hipSuccess) e = hipEventRecord(e1, c->stream);
+    if (!rc && e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (!rc && e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (!rc && e == hipSuccess) *ms_per_launch = (double)ms / reps;
+  }
+  c->prof = saved_prof;
+  c->n_ctx = -1;                 // the activation rows were overwritten
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (rc) return rc;
+  HIPCHK(c, e);
   return PPD_OK;
 }
 

@@ -171,3 +171,25 @@ def test_stream_read_probe_reports_a_plausible_rate():
     torch.cuda.synchronize()
     rate = binding.ppd_stream_read_probe(buf, iters=4)
     assert 1000.0 < rate < 8000.0, rate
+
+
+@pytest.mark.gpu
+def test_ffn_in_burst_timing_invalidates_the_sequence():
+    cfg = small_cfg("llama")
+    dev = binding.upload_model(pi.make_model(cfg))
+    P = binding.PPD(cfg, dev, k=3)
+    with pytest.raises(binding.PPDError) as ei:     # needs a prefilled context
+        P.ppd_time_ffn_in(4)
+    assert ei.value.code == -4
+    prompt = pi.make_prompt(cfg)
+    P.ppd_prefill(prompt)
+    ref = [P.ppd_step()[0] for _ in range(4)]
+    P.ppd_prefill(prompt)
+    ms = P.ppd_time_ffn_in(8)
+    assert 0.0 < ms < 1.0
+    with pytest.raises(binding.PPDError) as ei:     # the activations were overwritten
+        P.ppd_step()
+    assert ei.value.code == -4
+    P.ppd_prefill(prompt)                            # and a new prefill restores everything
+    assert [P.ppd_step()[0] for _ in range(4)] == ref
+    P.close()
