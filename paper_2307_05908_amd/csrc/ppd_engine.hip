@@ -323,7 +323,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages 
     mg.H = d.n_heads; mg.HD = d.head_dim; mg.d_model = dm; mg.nchunk_max = c->nchunk_max;
     int mmax = rg[0].M; if (ngroups == 2 && rg[1].M > mmax) mmax = rg[1].M;
     ProfScope ps(c, PPD_KC_ATTN_MERGE, ngroups);
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(mmax, d.n_heads, ngroups), dim3(d.head_dim), 0, c->cur, mg);
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(mmax, d.n_heads, ngroups), dim3(MERGE_THREADS), 0, c->cur, mg);
     HIPCHK(c, hipGetLastError());
   }
   // 3. output projection + residual

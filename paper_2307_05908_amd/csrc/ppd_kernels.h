@@ -779,38 +779,57 @@ struct MergeArgs {
   int H, HD, d_model, nchunk_max;
 };
 #ifdef PPD_ENGINE_TU
-__global__ void attn_merge_kernel(MergeArgs a) {
-  int g = blockIdx.z, h = blockIdx.y, m = blockIdx.x;
+constexpr int MERGE_THREADS = 512;
+// One workgroup per (row, head, group): thread t = component t % HD, slice t / HD.  Slice s merges the
+// chunks s, s + S, s + 2S, ... (S = MERGE_THREADS / HD slices) in that order with a running maximum,
+// 16 chunks' loads in flight together; then the slices are merged in slice order.
+__global__ __launch_bounds__(MERGE_THREADS) void attn_merge_kernel(MergeArgs a) {
+  __shared__ float sm_o[MERGE_THREADS], sl_m[8], sl_l[8];
+  const int g = blockIdx.z, h = blockIdx.y, m = blockIdx.x;
   if (m >= a.M[g]) return;
-  int nc = (a.ds->pos + a.pos_off[g]) / ATT_CHUNK + 1;
-  int i = threadIdx.x;
-  if (i >= a.HD) return;
+  const int nc = (a.ds->pos + a.pos_off[g]) / ATT_CHUNK + 1;
+  const int S = MERGE_THREADS / a.HD;          // 4 (head_dim 128) or 8 (64)
+  const int i = threadIdx.x % a.HD, sl = threadIdx.x / a.HD;
   const float* base = a.part[g] + (((size_t)m * a.H + h) * a.nchunk_max) * (a.HD + 2);
   const size_t cs = a.HD + 2;
   constexpr int UB = 16;    // chunks whose loads are in flight together
-  // running maximum over the batches; inside a batch every load is requested before anything is used
   float mx = -INFINITY, o = 0.f, l = 0.f;
-  for (int c0 = 0; c0 < nc; c0 += UB) {
+  for (int c0 = sl; c0 < nc; c0 += UB * S) {
     float tm[UB], ts[UB], to[UB];
 #pragma unroll
     for (int u = 0; u < UB; ++u) {
-      const float* pc = base + (size_t)(c0 + u < nc ? c0 + u : c0) * cs;
+      const int c = c0 + u * S;
+      const float* pc = base + (size_t)(c < nc ? c : c0) * cs;
       tm[u] = pc[a.HD]; ts[u] = pc[a.HD + 1]; to[u] = pc[i];
     }
     float bm = mx;
 #pragma unroll
-    for (int u = 0; u < UB; ++u) if (c0 + u < nc) bm = fmaxf(bm, tm[u]);
+    for (int u = 0; u < UB; ++u) if (c0 + u * S < nc) bm = fmaxf(bm, tm[u]);
     const float rescale = expf(mx - bm);     // 0 for the first batch (mx = -inf), 1 when the maximum stays
     o *= rescale; l *= rescale; mx = bm;
 #pragma unroll
     for (int u = 0; u < UB; ++u)
-      if (c0 + u < nc) {
-        float w = expf(tm[u] - mx);
+      if (c0 + u * S < nc) {
+        const float w = expf(tm[u] - mx);
         o = fmaf(w, to[u], o);
         l = fmaf(w, ts[u], l);
       }
   }
-  a.out[g][(size_t)m * a.d_model + (size_t)h * a.HD + i] = o / l;
+  // slices in order; a slice without chunks has mx = -inf and weight 0
+  sm_o[threadIdx.x] = o;
+  if (i == 0) { sl_m[sl] = mx; sl_l[sl] = l; }
+  __syncthreads();
+  if (sl == 0) {
+    float gm = -INFINITY;
+    for (int q = 0; q < S; ++q) gm = fmaxf(gm, sl_m[q]);
+    float oo = 0.f, ll = 0.f;
+    for (int q = 0; q < S; ++q) {
+      const float w = expf(sl_m[q] - gm);     // exp(-inf) = 0 for an empty slice
+      oo = fmaf(w, sm_o[q * a.HD + i], oo);
+      ll = fmaf(w, sl_l[q], ll);
+    }
+    a.out[g][(size_t)m * a.d_model + (size_t)h * a.HD + i] = oo / ll;
+  }
 }
 #endif
 
