@@ -40,6 +40,7 @@ struct ppd_ctx {
   // bf16 models: weights repacked into MFMA blocks (owned copies); fp32 models stream the caller's tensors
   int mfma;
   int mg_occ;            // workgroups of the MFMA GEMM a compute unit is asked to hold (1 or 2)
+  int mg_passes_min;     // least number of staging passes of launches without a fused norm (1; tests force more)
   struct LayerP { void *qkv, *o, *fin, *fout; };
   std::vector<LayerP> LP;
   void *head_p, *early_p;
@@ -185,10 +186,24 @@ constexpr size_t MG_LDS_MAX = 160 * 1024;
 // (each slice streams the weights again).
 hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
   a.KT = (a.K + 31) / 32;
-  a.xrow = mg_xrow(a.KT);
   if ((size_t)a.NT * a.KT * 1024 > 0x7fffffffu) return hipErrorInvalidValue;   // 32-bit offsets into one matrix
   a.wbytes = (unsigned)((size_t)a.NT * a.KT * 1024);
-  auto lds_for = [&](int M, int tiles) { int b, p, x; return (size_t)mg_lds_layout(a.K, M, a.norm, tiles, a.xrow, b, p, x); };
+  int mmax = a.g[0].M;
+  if (ngroups == 2 && a.g[1].M > mmax) mmax = a.g[1].M;
+  auto lds_with = [&](int M, int tiles, int passes) {
+    int b, p, x;
+    return (size_t)mg_lds_layout(a.K, M, a.norm, tiles, mg_xrow_pass(a.KT, passes), b, p, x);
+  };
+  // Passes over the reduction length: 1 when the staged rows of the largest group fit LDS (next to the
+  // partial sums of a one-workgroup-per-unit grid); launches without a fused norm otherwise stage the rows
+  // in the fewest passes that fit (same arithmetic, weights still read once).  Launches with a fused
+  // norm need whole rows: those fall back to row slices below.
+  const int t1 = a.topk > 0 ? (a.NT + c->head_grid - 1) / c->head_grid : (a.NT + 255) / 256;
+  a.passes = c->mg_passes_min;
+  if (a.norm >= 0) a.passes = 1;
+  else while (a.passes < 8 && lds_with(mmax, t1 * 2, a.passes) > MG_LDS_MAX) ++a.passes;
+  a.xrow = mg_xrow_pass(a.KT, a.passes);
+  auto lds_for = [&](int M, int tiles) { return lds_with(M, tiles, a.passes); };
   // Workgroups per group: the launch's share of the machine (two workgroups of 8 waves fit a compute
   // unit when their LDS does), then the smallest grid with the same number of tiles per workgroup, so
   // that all of them finish together.
@@ -208,14 +223,14 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
     const size_t lds = lds_for(mm, x.tiles_wg);
     if (lds > MG_LDS_MAX || (x.topk > 0 && x.tiles_wg * 16 > HEAD_MAX_ROWS)) return hipErrorInvalidValue;
     dim3 grid(gx, ng);
-    if (paired) hipLaunchKernelGGL(gemm_mfma_kernel<true>, grid, dim3(MG_THREADS), lds, c->cur, x);
-    else hipLaunchKernelGGL(gemm_mfma_kernel<false>, grid, dim3(MG_THREADS), lds, c->cur, x);
+    if (x.passes > 1) {
+      if (paired) return hipErrorInvalidValue;       // (paired launches carry a fused norm: always one pass)
+      hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), grid, dim3(MG_THREADS), lds, c->cur, x);
+    } else if (paired) hipLaunchKernelGGL((gemm_mfma_kernel<true, false>), grid, dim3(MG_THREADS), lds, c->cur, x);
+    else hipLaunchKernelGGL((gemm_mfma_kernel<false, false>), grid, dim3(MG_THREADS), lds, c->cur, x);
     return hipGetLastError();
   };
-  int mmax = a.g[0].M;
-  if (ngroups == 2 && a.g[1].M > mmax) mmax = a.g[1].M;
-  // rows whose staged form fits LDS next to the partial sums of a one-workgroup-per-unit grid
-  const int t1 = a.topk > 0 ? (a.NT + c->head_grid - 1) / c->head_grid : (a.NT + 255) / 256;
+  // rows whose staged form fits LDS
   int mcap = 0;
   while (mcap < 16 && lds_for(mcap + 1, t1 * 2) <= MG_LDS_MAX) ++mcap;
   if (mmax <= mcap) return go(a, ngroups, mmax);
@@ -722,11 +737,14 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     repack(c->lm_head, nullptr, nullptr, d.vocab, 0, 0, (int)dm, false, &c->head_p);
     if (c->early_head) repack(c->early_head, nullptr, nullptr, d.vocab, 0, 0, (int)dm, false, &c->early_p);
     if (e == hipSuccess) e = hipDeviceSynchronize();
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
     // head launches: the same balanced grid as any other GEMM; a workgroup keeps at most
     // HEAD_MAX_ROWS logits = 16 tiles
     c->mg_occ = env_int("PPD_MGOCC", 1) == 2 ? 2 : 1;
+    c->mg_passes_min = env_int("PPD_MGPASSES", 1);
+    if (c->mg_passes_min < 1 || c->mg_passes_min > 8) c->mg_passes_min = 1;
     const int NTh = (d.vocab + 15) / 16;
     int th = (NTh + 256 * c->mg_occ - 1) / (256 * c->mg_occ);
     c->head_grid = (NTh + th - 1) / th;

@@ -1040,11 +1040,20 @@ struct MGemmArgs {
   int xrow;         // LDS bytes between two staged rows
   int tiles_wg;     // ceil(NT / gridDim.x); gridDim.x <= NT
   unsigned wbytes;  // NT * KT * 1024
+  int passes;       // the reduction length is staged in LDS in this many passes (1: whole rows; > 1 only without a fused norm)
 };
 
 // LDS bytes between staged rows: the row itself, moved off a multiple of 256 so that neighbouring rows
 // start in different banks
 __host__ __device__ inline int mg_xrow(int KT) { int r = KT * 128; return (r & 255) ? r : r + 128; }
+// Staging in passes: every wave's share of the reduction length (nb8 blocks) is cut into `passes` runs of
+// nbp blocks (a multiple of the batch size); pass p stages, for each of the 8 waves, run p of its share.
+__host__ __device__ inline int mg_nbp(int KT, int passes) {
+  const int nb8 = (KT + MG_WAVES - 1) / MG_WAVES;
+  if (passes <= 1) return (nb8 + MG_BATCH - 1) / MG_BATCH * MG_BATCH;
+  return ((nb8 + passes - 1) / passes + MG_BATCH - 1) / MG_BATCH * MG_BATCH;
+}
+__host__ __device__ inline int mg_xrow_pass(int KT, int passes) { return passes <= 1 ? mg_xrow(KT) : mg_nbp(KT, passes) * 1024 + 128; }
 // LDS map behind MG_LDS_G; returns the total
 __host__ __device__ inline int mg_lds_layout(int K, int M, int norm, int tiles_wg, int xrow, int& off_b, int& off_part, int& off_x) {
   const int gsz = (K * 2 + 1023) & ~1023;
@@ -1054,7 +1063,9 @@ __host__ __device__ inline int mg_lds_layout(int K, int M, int norm, int tiles_w
   return off_x + M * xrow;
 }
 
-template <bool PAIRED>
+// MP: the instance that can stage the reduction length in several passes (a.passes > 1); the other one
+// keeps the single-pass loop free of that bookkeeping.
+template <bool PAIRED, bool MP = false>
 __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
   extern __shared__ float4 lds4[];
   char* lds = (char*)lds4;
@@ -1073,13 +1084,35 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
 
   // ---- 1. input rows (and the norm's gain and bias) into LDS, fp32 as they are: wave w takes the
   // kilobyte pieces w, w + 8, ... of every row.  These requests come first: a wave's loads return in order.
-  {
-    const int U = (K + 255) >> 8;
+  // With passes, a staged row is 8 runs (one per wave) of nbp blocks; float f of the row belongs to wave
+  // f / (32 nbp)'s share, block (pass * nbp + (f / 32) % nbp) of it.  pass_col gives the input column, or -1.
+  const int npass = MP ? a.passes : 1;
+  const int nb8_ = (KT + MG_WAVES - 1) / MG_WAVES, nbp_ = mg_nbp(KT, npass);
+  auto pass_col = [&](int pass, int f) -> int {
+    const int seg = f / (32 * nbp_), rem = f - seg * 32 * nbp_;
+    const int s = pass * nbp_ + (rem >> 5);
+    const int k0 = seg * nb8_ < KT ? seg * nb8_ : KT;
+    const int nb = (k0 + nb8_ < KT ? k0 + nb8_ : KT) - k0;
+    const int col = (k0 + s) * 32 + (rem & 31);
+    return (s < nb && col < K) ? col : -1;
+  };
+  auto dma_pass = [&](int pass) {
     for (int m = 0; m < M; ++m)
-      for (int u = wave; u < U; u += MG_WAVES) {
-        const int kk = u * 256 + lane * 4;
-        if (kk < K) dma16(G.X + (size_t)m * a.ldx + kk, lds + off_x + m * xrow + u * 1024);
+      for (int u = wave; u < nbp_; u += MG_WAVES) {
+        const int col = pass_col(pass, u * 256 + lane * 4);
+        if (col >= 0) dma16(G.X + (size_t)m * a.ldx + col, lds + off_x + m * xrow + u * 1024);
       }
+  };
+  {
+    if (MP && npass > 1) dma_pass(0);
+    else {
+      const int U = (K + 255) >> 8;
+      for (int m = 0; m < M; ++m)
+        for (int u = wave; u < U; u += MG_WAVES) {
+          const int kk = u * 256 + lane * 4;
+          if (kk < K) dma16(G.X + (size_t)m * a.ldx + kk, lds + off_x + m * xrow + u * 1024);
+        }
+    }
     if (a.norm >= 0) {
       const int Ug = (K + 511) >> 9;
       for (int u = wave; u < Ug; u += MG_WAVES) {
@@ -1137,20 +1170,39 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
   const int nb8 = (KT + MG_WAVES - 1) / MG_WAVES;
   const int kb0 = wave * nb8 < KT ? wave * nb8 : KT;
   const int nblk = (kb0 + nb8 < KT ? kb0 + nb8 : KT) - kb0;
-  const int NBT = (nb8 + MG_BATCH - 1) / MG_BATCH;           // batches per tile, the same for every wave
-  const int Q = ntiles * NBT;
+  // Passes (P > 1 when the staged rows would not fit LDS at once): pass p covers blocks [p * nbp, (p + 1) * nbp)
+  // of every wave's share, for all tiles, before the next pass starts.  A wave's accumulator of a tile is
+  // parked in its partial-sum slot between passes and taken up again as the MFMA's C input, so the chain of
+  // additions is exactly the one of a single pass.
+  const int P = npass;
+  const int nbp = mg_nbp(KT, P);                             // blocks of a wave's share per pass
+  const int NBT = MP ? nbp / MG_BATCH : (nb8 + MG_BATCH - 1) / MG_BATCH;   // batches per tile (and pass), the same for every wave
+  const int sst = P == 1 ? nb8 : nbp;                        // blocks between two waves' staged runs
+  const int Q = P * ntiles * NBT;
   const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void*)G.P, 0, (int)a.wbytes, 0x00020000);
   const unsigned lane16 = lane * 16;
-  int l_tile = 0, l_b = 0;     // tile ordinal and batch inside the tile of the next request
+  int l_p = 0, l_tile = 0, l_b = 0;     // pass, tile ordinal and batch inside the tile of the next request
   auto issue = [&](u32x4 (&buf)[MG_BATCH]) {
-    const bool live = l_tile < ntiles;
-    const unsigned base = (unsigned)(((int)blockIdx.x + l_tile * grid) * KT + kb0 + l_b * MG_BATCH) * 1024u;
+    if constexpr (!MP) {
+      const bool live = l_tile < ntiles;
+      const unsigned base = (unsigned)(((int)blockIdx.x + l_tile * grid) * KT + kb0 + l_b * MG_BATCH) * 1024u;
 #pragma unroll
-    for (int j = 0; j < MG_BATCH; ++j) {
-      const bool ok = live && l_b * MG_BATCH + j < nblk;
-      buf[j] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, ok ? base + j * 1024u : 0u, 2);   // 2: non-temporal
+      for (int j = 0; j < MG_BATCH; ++j) {
+        const bool ok = live && l_b * MG_BATCH + j < nblk;
+        buf[j] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, ok ? base + j * 1024u : 0u, 2);   // 2: non-temporal
+      }
+      if (++l_b == NBT) { l_b = 0; ++l_tile; }
+    } else {
+      const bool live = l_p < P;
+      const int s0 = l_p * nbp + l_b * MG_BATCH;
+      const unsigned base = (unsigned)(((int)blockIdx.x + l_tile * grid) * KT + kb0 + s0) * 1024u;
+#pragma unroll
+      for (int j = 0; j < MG_BATCH; ++j) {
+        const bool ok = live && s0 + j < nblk;
+        buf[j] = __builtin_amdgcn_raw_buffer_load_b128(wres, lane16, ok ? base + j * 1024u : 0u, 2);
+      }
+      if (++l_b == NBT) { l_b = 0; if (++l_tile == ntiles) { l_tile = 0; ++l_p; } }
     }
-    if (++l_b == NBT) { l_b = 0; ++l_tile; }
   };
   // One batch per wave is what a compute unit keeps in flight: it goes out now, the rest of the ring
   // after the rows are staged (a wave that asked for more would sit in the request queue instead of
@@ -1201,12 +1253,15 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
     }
     __syncthreads();
   }
+  // (with passes: the same split, for the runs of one pass; chunks outside every wave's share become zeros)
+  auto convert_rows = [&](int pass) {
+  const int nch = (MP && npass > 1) ? nbp_ * 32 : nchunk;
   for (int m = 0; m < M; ++m) {
     const float mu = a.norm >= 0 ? stat[m] : 0.f, rs = a.norm >= 0 ? stat[16 + m] : 1.f;
-    for (int c = tid; c < nchunk; c += MG_THREADS) {
+    for (int c = tid; c < nch; c += MG_THREADS) {
       char* px = lds + off_x + m * xrow + c * 32;
       float xv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      if (c * 8 < K) {
+      if ((MP && npass > 1) ? pass_col(pass, c * 8) >= 0 : c * 8 < K) {
         const float4 v = ((const float4*)px)[0], w = ((const float4*)px)[1];
         xv[0] = v.x; xv[1] = v.y; xv[2] = v.z; xv[3] = v.w; xv[4] = w.x; xv[5] = w.y; xv[6] = w.z; xv[7] = w.w;
         if (a.norm >= 0) {
@@ -1234,6 +1289,8 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
       ((uint4*)px)[1] = make_uint4(lp[0], lp[1], lp[2], lp[3]);
     }
   }
+  };
+  convert_rows(0);
   __syncthreads();
 #pragma unroll
   for (int r = 1; r < MG_RING; ++r) issue(ring[r]);
@@ -1241,27 +1298,59 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
   // ---- 5. main loop.  B operand: lane l feeds column l % 16 (input row; lanes past M read row 0 and
   // their columns are never stored) and the eight k of chunk l / 16.
   const int bm = lane & 15, bc = lane >> 4;
-  const char* xlane = lds + off_x + (bm < M ? bm : 0) * xrow + bc * 32 + kb0 * 128;
+  const char* xlane = lds + off_x + (bm < M ? bm : 0) * xrow + bc * 32 + ((!MP || P == 1) ? kb0 : wave * sst) * 128;
   float* plane = (float*)(lds + off_part) + (wave * M + bm) * 16 + bc * 4;   // + ord * 8 * M * 16
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  int c_ord = 0, c_b = 0;
+  int c_p = 0, c_ord = 0, c_b = 0;
   auto consume = [&](u32x4 (&cur)[MG_BATCH]) {
+    if constexpr (!MP) {
 #pragma unroll
-    for (int j = 0; j < MG_BATCH; ++j) {
-      const int s = c_b * MG_BATCH + j;
-      if (s < nblk) {                      // the same for the whole wave
-        const u32x4* xp = (const u32x4*)(xlane + s * 128);
-        const u32x4 bh = xp[0], bl = xp[1];
-        const bf16x8 av = __builtin_bit_cast(bf16x8, cur[j]);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl), acc, 0, 0, 0);
+      for (int j = 0; j < MG_BATCH; ++j) {
+        const int s = c_b * MG_BATCH + j;
+        if (s < nblk) {                      // the same for the whole wave
+          const u32x4* xp = (const u32x4*)(xlane + s * 128);
+          const u32x4 bh = xp[0], bl = xp[1];
+          const bf16x8 av = __builtin_bit_cast(bf16x8, cur[j]);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl), acc, 0, 0, 0);
+        }
       }
-    }
-    if (++c_b == NBT) {
-      // this wave's partial sums of the tile: lane l holds rows 4 (l / 16) .. + 3 of column l % 16
-      if (bm < M) *(f32x4*)(plane + c_ord * (MG_WAVES * 16) * M) = acc;
-      acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-      c_b = 0; ++c_ord;
+      if (++c_b == NBT) {
+        // this wave's partial sums of the tile: lane l holds rows 4 (l / 16) .. + 3 of column l % 16
+        if (bm < M) *(f32x4*)(plane + c_ord * (MG_WAVES * 16) * M) = acc;
+        acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        c_b = 0; ++c_ord;
+      }
+    } else {
+      if (c_b == 0 && c_p > 0) {
+        if (c_ord == 0) {
+          // next pass: every wave is done with the staged runs; bring in the next ones (the weight requests
+          // already made for this pass keep flying meanwhile)
+          __syncthreads();
+          dma_pass(c_p);
+          asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+          convert_rows(c_p);
+          __syncthreads();
+        }
+        if (bm < M) acc = *(const f32x4*)(plane + c_ord * (MG_WAVES * 16) * M);    // the chain goes on where it stopped
+      }
+#pragma unroll
+      for (int j = 0; j < MG_BATCH; ++j) {
+        const int s = c_p * nbp + c_b * MG_BATCH + j;
+        if (s < nblk) {
+          const u32x4* xp = (const u32x4*)(xlane + (s - c_p * nbp) * 128);
+          const u32x4 bh = xp[0], bl = xp[1];
+          const bf16x8 av = __builtin_bit_cast(bf16x8, cur[j]);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, bl), acc, 0, 0, 0);
+        }
+      }
+      if (++c_b == NBT) {
+        if (bm < M) *(f32x4*)(plane + c_ord * (MG_WAVES * 16) * M) = acc;
+        acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        c_b = 0;
+        if (++c_ord == ntiles) { c_ord = 0; ++c_p; }
+      }
     }
   };
   for (int q = 0; q < Q; q += MG_RING) {

@@ -193,3 +193,31 @@ def test_ffn_in_burst_timing_invalidates_the_sequence():
     P.ppd_prefill(prompt)                            # and a new prefill restores everything
     assert [P.ppd_step()[0] for _ in range(4)] == ref
     P.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("family", ["llama", "opt"])
+def test_staging_in_passes_is_bit_identical(family, monkeypatch):
+    """Rows too long for LDS are staged in several passes with the accumulators parked in between; forced on
+    here (PPD_MGPASSES), every token and logit equals the single-pass run bit for bit."""
+    cfg = small_cfg(family)
+    dev = binding.upload_model(pi.make_model(cfg))
+    prompt = pi.make_prompt(cfg)
+
+    def run():
+        P = binding.PPD(cfg, dev, k=5)
+        P.ppd_prefill(prompt)
+        toks, zs = [], []
+        for _ in range(cfg.n_gen):
+            toks.append(P.ppd_step()[0])
+            zs.append(P.ppd_get_logits().copy())
+        P.close()
+        return toks, np.stack(zs)
+
+    ref_t, ref_z = run()
+    for passes in (2, 3):
+        monkeypatch.setenv("PPD_MGPASSES", str(passes))
+        t, z = run()
+        assert t == ref_t
+        np.testing.assert_array_equal(z.view(np.uint32), ref_z.view(np.uint32))
+    monkeypatch.delenv("PPD_MGPASSES")
