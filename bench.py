@@ -206,6 +206,8 @@ def main():
         "plain_greedy": {"tokens_per_s": round(K / wall_plain, 2), "ms_per_token": round(wall_plain / K * 1e3, 4)},
         "ppd_vs_plain_speed": round(wall_plain / wall_ppd, 4),
         "p_correct": round(p_hat, 4),
+        "lm_head_passes_per_round": round((st["weight_bytes"] - (st["main_layer_rows"] + (cfg.n_layers - e) * ell) * wl)
+                                          / (cfg.vocab * cfg.d_model * cfg.wbytes) / ell, 4),
         "layer_rows_per_token": {"measured_main": st["main_layer_rows"] / ell,
                                  "measured_total": (st["main_layer_rows"] + st["branch_layer_rows"]) / ell,
                                  "theorem_latency": tradeoff.expected_latency(d, e, ell, p_hat) / ell,

@@ -145,7 +145,13 @@ int ppd_prefill(ppd_ctx *ctx, const int32_t *prompt, int n_prompt);
  * Writes the emitted token to out_tokens[0] (HOST, max_out >= 1) and returns
  * the number of tokens written: 1, or 0 once the previous token was EOS.
  * info (HOST, nullable) receives the round's record.  PPD_ECTX when position
- * t+1 would not fit in max_ctx.  Synchronous: the stream is idle on return. */
+ * t+1 would not fit in max_ctx.  Synchronous: the stream is idle on return.
+ * When exit_layer = d/2 and w->early_head is NULL (bf16 weights), the candidate
+ * rows finish a round at the exit layer, so the round's final LM-head pass also
+ * covers them; after a match the matching row's top-k are the next round's
+ * candidates and that round runs no early head of its own (same candidates,
+ * logits and tokens; one LM-head pass less).  PPD_SPEC=2 in the environment
+ * at ppd_create switches this off. */
 int ppd_step(ppd_ctx *ctx, int32_t *out_tokens, int max_out, ppd_step_info *info);
 
 /* Conventional decoding of one token (Sec. 4.2: d time units per token): all

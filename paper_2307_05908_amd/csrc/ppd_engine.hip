@@ -53,8 +53,16 @@ struct ppd_ctx {
   float *att;            // [1+k][d_model]
   float *ffn;            // [1+k][d_ff]
   float *part;           // [1+k][H][nchunk_max][hd+2]
-  float *logits, *early_logits;  // [vocab]
-  float *pk_val; int32_t *pk_idx; // [head_grid][MAXM] block top-k candidates of the head GEMM
+  float *logits, *early_logits;  // [1 + k][vocab] (row 0: the main token's), [vocab]
+  float *early_spec;             // [2][vocab] early logits predicted at the end of the previous round (spec)
+  float *pk_val; int32_t *pk_idx; // [1 + k][pk_slots][MAXM] block top-k candidates of the head GEMM, per row
+  size_t pk_slots;
+  // Speculative early prediction: with the exit layer at d/2 and no separate early head, the candidate
+  // rows end a round exactly where the next round's early prediction reads the main row.  The final head
+  // then runs on all 1 + k rows; after a match the matching row's top-k are the next candidates and the
+  // next round (kind 3) starts with its parallel phase: one head pass per matching round instead of two.
+  int spec;
+  int last_kind;
   int head_grid;
   float2 *rope;          // [max_ctx][hd/2]
   DevState *ds;
@@ -63,8 +71,8 @@ struct ppd_ctx {
   int32_t *host_result_dev; // the same memory as the GPU sees it
   // captured rounds: 0 ppd round from layer 1, 1 ppd round after a match, 2 plain step
   int use_graphs;
-  hipGraphExec_t graph[3];
-  int graph_chunks[3];   // attention grid (128-position chunks) each graph was captured with
+  hipGraphExec_t graph[4];
+  int graph_chunks[4];   // attention grid (128-position chunks) each graph was captured with
   int gmax1, gmax2, gmaxd; // workgroup budget of a GEMM launch: one group / per group of a two-group launch / per chain of the parallel phase
   int in_dual;           // launches belong to one of two concurrent chains
   int skew;              // the candidates' chain starts half a layer after the main token's
@@ -203,7 +211,9 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
   if (a.norm >= 0) a.passes = 1;
   else while (a.passes < 8 && lds_with(mmax, t1 * 2, a.passes) > MG_LDS_MAX) ++a.passes;
   a.xrow = mg_xrow_pass(a.KT, a.passes);
-  auto lds_for = [&](int M, int tiles) { return lds_with(M, tiles, a.passes); };
+  // head launches keep HEAD_MAX_ROWS logits per row where the staged rows were
+  if (a.topk > 0 && a.xrow < HEAD_MAX_ROWS * (int)sizeof(float)) a.xrow = HEAD_MAX_ROWS * (int)sizeof(float);
+  auto lds_for = [&](int M, int tiles) { int b, p, x; return (size_t)mg_lds_layout(a.K, M, a.norm, tiles, a.xrow, b, p, x); };
   // Workgroups per group: the launch's share of the machine (two workgroups of 8 waves fit a compute
   // unit when their LDS does), then the smallest grid with the same number of tiles per workgroup, so
   // that all of them finish together.
@@ -232,7 +242,9 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
   };
   // rows whose staged form fits LDS
   int mcap = 0;
-  while (mcap < 16 && lds_for(mcap + 1, t1 * 2) <= MG_LDS_MAX) ++mcap;
+  const int tcap = a.topk > 0 ? t1 : t1 * 2;
+  while (mcap < 16 && lds_for(mcap + 1, tcap) <= MG_LDS_MAX) ++mcap;
+  if (a.topk > 0 && mmax > mcap) return hipErrorInvalidValue;   // head launches are never cut into row slices
   if (mmax <= mcap) return go(a, ngroups, mmax);
   if (mcap < 1) return hipErrorInvalidValue;
   for (int g = 0; g < ngroups; ++g) {
@@ -271,7 +283,7 @@ hipError_t mgemm_from(ppd_ctx* c, const GemmArgs& a, int ngroups, bool paired, v
   m.K = a.K; m.N[0] = a.N[0]; m.N[1] = a.N[1]; m.N[2] = a.N[2]; m.ntot = a.ntot;
   m.NT = paired ? (a.ntot + 7) / 8 : (a.ntot + 15) / 16;
   m.ldx = a.ldx; m.ldy = a.ldy; m.norm = a.norm; m.eps = a.eps; m.act = a.act == 3 ? 0 : a.act;
-  m.topk = a.topk; m.pk_val = a.pk_val; m.pk_idx = a.pk_idx;
+  m.topk = a.topk; m.pk_val = a.pk_val; m.pk_idx = a.pk_idx; m.pk_stride = (int)c->pk_slots;
   return launch_mgemm(c, m, ngroups, paired);
 }
 
@@ -416,8 +428,8 @@ int run_embed(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos_of
   return PPD_OK;
 }
 
-int set_state(ppd_ctx* c, int pos, int tok) {
-  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->cur, c->ds, pos, tok);
+int set_state(ppd_ctx* c, int pos, int tok, int take_next = 0) {
+  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->cur, c->ds, pos, tok, take_next);
   HIPCHK(c, hipGetLastError());
   return PPD_OK;
 }
@@ -425,17 +437,19 @@ int set_state(ppd_ctx* c, int pos, int tok) {
 // Final norm + LM head on the main row with every workgroup's own top-k, then the selection
 // kernel.  early: top-k -> candidates, which it also embeds as rows 1..k at the next position.
 // final: arg max, verification; with adopt, the matching candidate's row and KV tails are adopted.
+// With speculative early prediction the adopting head also runs on the candidate rows (see ppd_ctx::spec).
 int run_head(ppd_ctx* c, bool early, bool adopt) {
   const ppd_model_dims& d = c->d;
+  const bool spec = c->spec && adopt && !early;
   {
     GemmArgs a; memset(&a, 0, sizeof a);
     GemmGroup& G = a.g[0];
     G.X = c->h; G.Y = early ? c->early_logits : c->logits; G.Rsd = nullptr;
     G.W[0] = (early && c->early_head) ? c->early_head : c->lm_head;
-    G.ng = c->lnf_g; G.nb = d.norm == 0 ? c->lnf_b : nullptr; G.M = 1;
+    G.ng = c->lnf_g; G.nb = d.norm == 0 ? c->lnf_b : nullptr; G.M = spec ? 1 + c->k : 1;
     a.K = d.d_model; a.N[0] = d.vocab; a.ntot = d.vocab; a.ldx = d.d_model; a.ldy = d.vocab;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
-    a.topk = early ? c->k : 1; a.pk_val = c->pk_val; a.pk_idx = c->pk_idx;
+    a.topk = (early || spec) ? c->k : 1; a.pk_val = c->pk_val; a.pk_idx = c->pk_idx;
     ProfScope ps(c, PPD_KC_HEAD);
     if (c->mfma) {
       void* P[2] = {(early && c->early_p) ? c->early_p : c->head_p, nullptr};
@@ -444,7 +458,8 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     HIPCHK(c, launch_gemm(c, a, 1, false));
   }
   SelectArgs s; memset(&s, 0, sizeof s);
-  s.pk_val = c->pk_val; s.pk_idx = c->pk_idx; s.nblk = c->head_grid; s.kk = early ? c->k : 1;
+  s.pk_val = c->pk_val; s.pk_idx = c->pk_idx; s.nblk = c->head_grid; s.kk = (early || spec) ? c->k : 1;
+  s.pk_stride = (int)c->pk_slots;
   s.k = adopt || early ? c->k : 0; s.mode = early ? 0 : 1; s.ds = c->ds; s.host_result = c->host_result_dev;
   dim3 grid(1, 1);
   if (early) {
@@ -454,7 +469,13 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     s.h = c->h; s.tailK = (const float*)c->tailK; s.tailV = (const float*)c->tailV; s.Kc = (float*)c->Kc; s.Vc = (float*)c->Vc;
     s.head_floats = cache_head_floats(c);
     s.nb = c->nb; s.H = d.n_heads; s.hd = d.head_dim; s.d_model = d.d_model; s.max_ctx = d.max_ctx;
-    grid = dim3(c->nb, 2);
+    if (spec) {
+      s.spec = 1; s.spec_logits = c->logits + d.vocab; s.early_spec = c->early_spec; s.vocab = d.vocab;
+      s.emb = embed_args(c, nullptr, c->k, 1, 2);
+    }
+    // tail blocks, then (spec) blocks that copy the logits row / embed the next candidates, a column per thread
+    const int extra = spec ? (d.d_model + SEL_THREADS - 1) / SEL_THREADS : 0;
+    grid = dim3(c->nb + (extra > 16 ? 16 : extra), 2);
   }
   ProfScope ps(c, PPD_KC_SELECT);
   if (c->wbytes == 4) hipLaunchKernelGGL(select_kernel<float>, grid, dim3(SEL_THREADS), 0, c->cur, s);
@@ -465,7 +486,8 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
 
 // The launches of one round.  kind 0: PPD round from layer 1 (after a miss or a prefill);
 // kind 1: PPD round after a match (layers 1..d-dbar were run by the matching candidate row);
-// kind 2: plain greedy step.  pmax bounds the positions touched (attention grid size only).
+// kind 2: plain greedy step; kind 3: PPD round after a match whose candidates the previous round's final head
+// already predicted and embedded (speculative early prediction): parallel phase and final head only.  pmax bounds the positions touched (attention grid size only).
 int issue_round(ppd_ctx* c, int kind, int pmax) {
   const int d = c->d.n_layers, dbar = c->dbar, nb = c->nb, k = c->k;
   int rc;
@@ -478,7 +500,7 @@ int issue_round(ppd_ctx* c, int kind, int pmax) {
     return run_head(c, false, false);
   }
   // main token up to the exit layer
-  int from = kind == 1 ? nb : 0;
+  int from = (kind == 1 || kind == 3) ? nb : 0;
   if (kind == 0 && (rc = run_embed(c, &c->ds->next_tok, 1, 0, 0))) return rc;
   if (from < dbar) {
     ProfScope phase(c, PPD_KC_PHASE, 1);
@@ -488,7 +510,7 @@ int issue_round(ppd_ctx* c, int kind, int pmax) {
     }
   }
   // early prediction; the candidates become rows 1..k at the next position
-  if ((rc = run_head(c, true, false))) return rc;
+  if (kind != 3 && (rc = run_head(c, true, false))) return rc;
   // parallel phase: step j runs the main row at layer dbar+j and the candidates at layer j
   if (c->dual) {
     // two concurrent chains, one per stream: while one chain sits in a latency-bound stretch
@@ -533,7 +555,7 @@ int run_round(ppd_ctx* c, int kind, int pos) {
   int rc;
   HIPCHK(c, hipEventRecord(c->join_ev, c->user_stream));
   HIPCHK(c, hipStreamWaitEvent(c->stream, c->join_ev, 0));
-  if ((rc = set_state(c, pos, -1))) return rc;
+  if ((rc = set_state(c, pos, -1, kind == 3))) return rc;
   const int pmax = pos + (kind == 2 ? 0 : 1);
   if (c->use_graphs && !c->prof) {
     const int nchunks = pmax / ATT_CHUNK + 1;
@@ -573,15 +595,15 @@ void account_round(ppd_ctx* c, int kind, int pos) {
     c->st.kv_bytes += (uint64_t)d.n_layers * pos * kvp;
     return;
   }
-  const int solo = c->dbar - (kind == 1 ? c->nb : 0);
-  c->st.weight_bytes += (uint64_t)(solo + 2 * c->nb) * wl + 2 * wh;
+  const int solo = c->dbar - (kind == 0 ? 0 : c->nb);
+  c->st.weight_bytes += (uint64_t)(solo + 2 * c->nb) * wl + (kind == 3 ? 1 : 2) * wh;
   c->st.kv_bytes += (uint64_t)(solo + c->nb) * pos * kvp + (uint64_t)c->nb * (pos + 1) * kvp;
 }
 
 void free_all(ppd_ctx* c) {
-  for (int i = 0; i < 3; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
+  for (int i = 0; i < 4; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
-                 c->early_logits, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
+                 c->early_logits, c->early_spec, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
@@ -675,11 +697,13 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   alloc((void**)&c->att, R * dm * sizeof(float));
   alloc((void**)&c->ffn, R * (size_t)d.d_ff * sizeof(float));
   alloc((void**)&c->part, R * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
-  alloc((void**)&c->logits, (size_t)d.vocab * sizeof(float));
+  alloc((void**)&c->logits, R * d.vocab * sizeof(float));
+  alloc((void**)&c->early_spec, (size_t)2 * d.vocab * sizeof(float));
   alloc((void**)&c->early_logits, (size_t)d.vocab * sizeof(float));
   const size_t pk_slots = (size_t)(c->head_grid > (d.vocab + 255) / 256 ? c->head_grid : (d.vocab + 255) / 256) + 1024;   // room for either head grid
-  alloc((void**)&c->pk_val, pk_slots * MAXM * sizeof(float));
-  alloc((void**)&c->pk_idx, pk_slots * MAXM * sizeof(int32_t));
+  c->pk_slots = pk_slots;
+  alloc((void**)&c->pk_val, R * pk_slots * MAXM * sizeof(float));
+  alloc((void**)&c->pk_idx, R * pk_slots * MAXM * sizeof(int32_t));
   alloc((void**)&c->ds, sizeof(DevState));
   alloc((void**)&c->prompt_dev, (size_t)d.max_ctx * sizeof(int32_t));
   if (d.pos == 1) alloc((void**)&c->rope, (size_t)d.max_ctx * (d.head_dim / 2) * sizeof(float2));
@@ -751,6 +775,16 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     while ((NTh + c->head_grid - 1) / c->head_grid > HEAD_MAX_ROWS / 16) ++c->head_grid;
     if ((size_t)c->head_grid > pk_slots) e = hipErrorInvalidValue;
     if (env_int("PPD_DUAL", 2) != 1) c->dual = 0;   // one launch per step for both chains unless asked otherwise
+    // speculative early prediction when the candidates end a round at the exit layer, the early head is the LM
+    // head, and the 1 + k rows of the widened final head fit one launch (PPD_SPEC=2 switches it off)
+    {
+      const int KT = ((int)dm + 31) / 32;
+      int xrow = mg_xrow(KT);
+      if (xrow < HEAD_MAX_ROWS * (int)sizeof(float)) xrow = HEAD_MAX_ROWS * (int)sizeof(float);
+      int ob, op, ox;
+      const size_t need = (size_t)mg_lds_layout((int)dm, 1 + k, d.norm, (NTh + c->head_grid - 1) / c->head_grid, xrow, ob, op, ox);
+      c->spec = 2 * c->dbar == d.n_layers && !c->early_head && need <= MG_LDS_MAX && env_int("PPD_SPEC", 1) != 2;
+    }
   }
   if (e != hipSuccess) {
     g_create_hip_error = (int)e;
@@ -806,17 +840,18 @@ int ppd_step(ppd_ctx* c, int32_t* out_tokens, int max_out, ppd_step_info* info) 
   if (c->finished) return 0;
   const int pos = c->n_ctx;
   if (pos + 1 >= c->d.max_ctx) return PPD_ECTX;   // the candidates sit at position pos+1
-  const int kind = c->matched ? 1 : 0;
+  const int kind = c->matched ? (c->spec ? 3 : 1) : 0;
   int rc = run_round(c, kind, pos);
   if (rc) return rc;
   account_round(c, kind, pos);
   const int tok = c->host_result[0], midx = c->host_result[1];
   if (kind == 0) c->st.runs += 1;
-  c->st.main_layer_rows += (uint64_t)(c->dbar - (kind == 1 ? c->nb : 0)) + c->nb;
+  c->st.main_layer_rows += (uint64_t)(c->dbar - (kind == 0 ? 0 : c->nb)) + c->nb;
   c->st.branch_layer_rows += (uint64_t)c->k * c->nb;
   c->n_ctx = pos + 1;
   c->matched = midx >= 0;
   c->have_early = 1;
+  c->last_kind = kind;
   c->st.rounds += 1;
   c->st.matches += c->matched;
   if (tok == c->d.eos_id) c->finished = 1;
@@ -841,6 +876,7 @@ int plain_greedy_step(ppd_ctx* c, int32_t* out_token) {
   account_round(c, 2, pos);
   c->n_ctx = pos + 1;
   c->matched = 0;
+  c->last_kind = 2;
   c->st.plain_steps += 1;
   if (c->host_result[0] == c->d.eos_id) c->finished = 1;
   *out_token = c->host_result[0];
@@ -857,7 +893,10 @@ int ppd_get_logits(ppd_ctx* c, float* host_logits) {
 int ppd_get_early_logits(ppd_ctx* c, float* host_logits) {
   if (!c || !host_logits) return PPD_EINVAL;
   if (c->n_ctx < 0 || !c->have_early) return PPD_ESTATE;
-  HIPCHK(c, hipMemcpy(host_logits, c->early_logits, (size_t)c->d.vocab * sizeof(float), hipMemcpyDeviceToHost));
+  // a round that started from a speculative prediction has its early logits in the half of early_spec that
+  // its position's parity selects (the position of the last round's main token is n_ctx - 1)
+  const float* src = c->last_kind == 3 ? c->early_spec + (size_t)((c->n_ctx - 1) & 1) * c->d.vocab : c->early_logits;
+  HIPCHK(c, hipMemcpy(host_logits, src, (size_t)c->d.vocab * sizeof(float), hipMemcpyDeviceToHost));
   return PPD_OK;
 }
 

@@ -44,6 +44,7 @@ struct DevState {
   int32_t next_tok;   // id of x_t
   int32_t result[2];  // token x_{t+1}, match_idx of the last final selection
   int32_t cand[MAXM]; // early top-k ids
+  int32_t cand_next[MAXM]; // candidates of the next round, predicted at the end of a matching round
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
@@ -138,8 +139,10 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* p, size_t
   for (; i < n16; i += stride) acc ^= ld_stream(p + i);
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) *sink = acc.x;   // keeps the loads alive; practically never taken
 }
-__global__ void set_state_kernel(DevState* ds, int pos, int tok) {
+// take_next: the round about to start uses the candidates the previous round predicted for it
+__global__ void set_state_kernel(DevState* ds, int pos, int tok, int take_next) {
   if (threadIdx.x == 0) { ds->pos = pos; if (tok >= 0) ds->next_tok = tok; }
+  if (take_next && threadIdx.x < MAXM) ds->cand[threadIdx.x] = ds->cand_next[threadIdx.x];
 }
 #endif
 
@@ -855,6 +858,16 @@ struct SelectArgs {
   float* Kc; float* Vc;     // [L][H][blocks][hd/16][64][4]
   size_t head_floats;       // floats of one head's cache
   int nb, H, hd, d_model, max_ctx;
+  // speculative early prediction (mode 1, exit layer d/2, early head = LM head): the head pass that made the
+  // final logits of row 0 also made, for every candidate row, the early logits of the next round (the
+  // candidate's state after d/2 layers is that round's exit-layer state).  On a match the matching row's
+  // top-k become the next candidates here and now, and the next round starts with its parallel phase.
+  int spec;
+  int pk_stride;            // block lists of row m start at (m * pk_stride) * MAXM
+  const float* spec_logits; // [k][vocab] logits of the candidate rows
+  float* early_spec;        // [2][vocab]: the matching row's logits are kept as the early logits of the round at
+                            // the next position, in the half that position's parity selects
+  int vocab;
 };
 constexpr int SEL_THREADS = 256;
 
@@ -866,7 +879,10 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   __shared__ int win[MAXM];
   __shared__ int s_midx;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nk = a.mode == 0 ? a.k : 1;
+  // merge of one row's block lists: the best nk by (value descending, id ascending) land in win[]
+  auto merge_row = [&](int prow, int nk) {
+  const float* pkv = a.pk_val + (size_t)prow * a.pk_stride * MAXM;
+  const int32_t* pki = a.pk_idx + (size_t)prow * a.pk_stride * MAXM;
   const int total = a.nblk * a.kk;
   // each thread scans its strided share and keeps its own sorted best nk
   float lv[MAXM]; int li[MAXM];
@@ -874,7 +890,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   for (int q = 0; q < MAXM; ++q) { lv[q] = -INFINITY; li[q] = 0x7fffffff; }
   for (int e = tid; e < total; e += SEL_THREADS) {
     int b = e / a.kk, r = e - b * a.kk;
-    float v = a.pk_val[b * MAXM + r]; int i = a.pk_idx[b * MAXM + r];
+    float v = pkv[b * MAXM + r]; int i = pki[b * MAXM + r];
     if (better(v, i, lv[MAXM - 1], li[MAXM - 1])) {
       lv[MAXM - 1] = v; li[MAXM - 1] = i;
 #pragma unroll
@@ -905,6 +921,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
     if (cur == wid) ++head;     // ids are unique: only the owner of the winner moves on
   }
   __syncthreads();
+  };
+  merge_row(0, a.mode == 0 ? a.k : 1);
   if (a.mode == 0) {
     // candidates and their rows; block x handles row blockIdx.y
     if (blockIdx.x == 0 && blockIdx.y == 0 && tid < a.k) a.ds->cand[tid] = win[tid];
@@ -933,11 +951,39 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
     a.host_result[0] = token; a.host_result[1] = midx;
   }
   if (midx < 0 || a.nb == 0) return;
-  // adoption: block (l, which) copies one layer's K or V tail; block (0,0) also the hidden row
+  // adoption: block (l, which), l < nb, copies one layer's K or V tail; block (0,0) also the hidden row.
+  // With speculative early prediction the grid has further blocks (l >= nb) that prepare the next round.
   const int l = blockIdx.x;
-  if (l >= a.nb) return;
   const int pos_next = a.ds->pos + 1;
-  if (l == 0 && blockIdx.y == 0)
+  if (l >= a.nb) {
+    if (!a.spec) return;
+    const int b = l - a.nb, nblocks = gridDim.x - a.nb;
+    if (blockIdx.y == 0) {
+      // the matching row's logits are the next round's early logits
+      const float* src = a.spec_logits + (size_t)midx * a.vocab;
+      float* dst = a.early_spec + (size_t)(pos_next & 1) * a.vocab;
+      for (int i = b * SEL_THREADS + tid; i < a.vocab; i += nblocks * SEL_THREADS) dst[i] = src[i];
+      return;
+    }
+    // the next round's candidates: top-k of the matching row's logits; then, column by column (each thread
+    // its own columns, so no thread waits for another): the matching row becomes row 0, and the candidates'
+    // embeddings become rows 1..k, one position on
+    merge_row(1 + midx, a.k);
+    if (b == 0 && tid < a.k) a.ds->cand_next[tid] = win[tid];
+    const EmbedArgs e = a.emb;
+    const int pos2 = pos_next + 1;
+    for (int i = b * SEL_THREADS + tid; i < a.d_model; i += nblocks * SEL_THREADS) {
+      a.h[i] = a.h[(size_t)(1 + midx) * a.d_model + i];
+      if (pos2 < a.max_ctx)
+        for (int r = 0; r < a.k; ++r) {
+          float v = WTr<WT>::load1(e.tok_emb, (size_t)win[r] * e.d_model + i);
+          if (e.pos_emb) v += WTr<WT>::load1(e.pos_emb, (size_t)pos2 * e.d_model + i);
+          e.h[(size_t)r * e.d_model + i] = v;
+        }
+    }
+    return;
+  }
+  if (!a.spec && l == 0 && blockIdx.y == 0)
     for (int i = tid; i < a.d_model; i += SEL_THREADS) a.h[i] = a.h[(size_t)(1 + midx) * a.d_model + i];
   // tails are [nb][k][H][hd] rows; the cache is blocked (k_index / v_index)
   const float* src = (blockIdx.y == 0 ? a.tailK : a.tailV) + ((size_t)l * a.k + midx) * a.d_model;
@@ -1036,7 +1082,8 @@ struct MGemmArgs {
   int norm;         // -1 none, 0 LayerNorm, 1 RMSNorm
   float eps;
   int act;          // 0 none, 1 GELU, 2 ReLU (paired launches apply SwiGLU)
-  int topk; float* pk_val; int32_t* pk_idx;
+  int topk; float* pk_val; int32_t* pk_idx;   // head launches: every workgroup leaves the top-k of each row's logits it made:
+  int pk_stride;    // row m's list of workgroup b at ((m * pk_stride + b) * MAXM)
   int xrow;         // LDS bytes between two staged rows
   int tiles_wg;     // ceil(NT / gridDim.x); gridDim.x <= NT
   unsigned wbytes;  // NT * KT * 1024
@@ -1080,7 +1127,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
   float* stat = (float*)lds;                  // mu[16], rstd[16], redA[16][8], redB[16][8]
   float* redA = stat + 32;
   float* redB = stat + 32 + 16 * MG_WAVES;
-  float* hlog = (float*)(lds + MG_LDS_HLOG);
+  float* hlog = (float*)(lds + off_x);        // head launches: [M][HEAD_MAX_ROWS] logits, over the staged rows once those are done with
 
   // ---- 1. input rows (and the norm's gain and bias) into LDS, fp32 as they are: wave w takes the
   // kilobyte pieces w, w + 8, ... of every row.  These requests come first: a wave's loads return in order.
@@ -1385,7 +1432,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
     }
     y += rsd;
     G.Y[(size_t)col * a.ldy + n] = y;
-    if (a.topk > 0 && col == 0) hlog[ord * 16 + row] = y;
+    if (a.topk > 0) hlog[col * HEAD_MAX_ROWS + ord * 16 + row] = y;
   };
 #pragma unroll
   for (int i = 0; i < MG_EP; ++i) {
@@ -1399,10 +1446,10 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
     finish(e, b0, b1, rsd);
   }
 
-  // ---- LM head: this workgroup's top-k by (logit descending, id ascending)
+  // ---- LM head: this workgroup's top-k of every row by (logit descending, id ascending); wave w takes rows w, w + 8, ...
   if (a.topk > 0) {
     __syncthreads();
-    if (wave == 0) {
+    for (int col = wave; col < M; col += MG_WAVES) {
       constexpr int EPL = HEAD_MAX_ROWS / WAVE;
       float ev[EPL]; int ei[EPL];
 #pragma unroll
@@ -1410,7 +1457,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
         const int e = lane + u * WAVE;       // entry e = tile ordinal * 16 + row
         ev[u] = -INFINITY; ei[u] = 0x7fffffff;
         const int id = ((int)blockIdx.x + (e >> 4) * grid) * 16 + (e & 15);
-        if ((e >> 4) < ntiles && id < a.ntot) { ev[u] = hlog[e]; ei[u] = id; }
+        if ((e >> 4) < ntiles && id < a.ntot) { ev[u] = hlog[col * HEAD_MAX_ROWS + e]; ei[u] = id; }
       }
       for (int r = 0; r < a.topk; ++r) {
         float v = -INFINITY; int i = 0x7fffffff;
@@ -1419,7 +1466,10 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
         wave_best(v, i);
 #pragma unroll
         for (int u = 0; u < EPL; ++u) if (ei[u] == i) { ev[u] = -INFINITY; ei[u] = 0x7fffffff; }
-        if (lane == 0) { a.pk_val[blockIdx.x * MAXM + r] = v; a.pk_idx[blockIdx.x * MAXM + r] = i; }
+        if (lane == 0) {
+          const size_t o = ((size_t)col * a.pk_stride + blockIdx.x) * MAXM + r;
+          a.pk_val[o] = v; a.pk_idx[o] = i;
+        }
       }
     }
   }

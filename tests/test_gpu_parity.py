@@ -221,3 +221,50 @@ def test_staging_in_passes_is_bit_identical(family, monkeypatch):
         assert t == ref_t
         np.testing.assert_array_equal(z.view(np.uint32), ref_z.view(np.uint32))
     monkeypatch.delenv("PPD_MGPASSES")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("family", ["llama", "opt", "llama_long"])
+@pytest.mark.parametrize("k", [1, 3, 5])
+def test_speculative_early_prediction_changes_nothing_but_the_traffic(family, k, monkeypatch):
+    """With the exit layer at d/2 the final head also runs on the candidate rows, and after a match the
+    matching row's top-k are the next round's candidates (no early head pass in that round).  Tokens, final
+    and early logits, candidates and match indices equal the rounds that run their own early head, bit for
+    bit; only the LM-head traffic drops, by one matrix per matching round."""
+    cfg = SMALL[family].replace(alpha=0.05)          # late layers damped: most early predictions hold
+    assert 2 * cfg.exit_layer == cfg.n_layers
+    dev = binding.upload_model(pi.make_model(cfg))
+    prompt = pi.make_prompt(cfg)
+
+    def run():
+        P = binding.PPD(cfg, dev, k=k)
+        P.ppd_prefill(prompt)
+        toks, zs, es, infos = [], [], [], []
+        for t in range(cfg.n_gen):
+            if t == cfg.n_gen // 2:                  # a plain step in between: the next round starts from layer 1 again
+                toks.append(P.plain_greedy_step())
+                continue
+            tok, info = P.ppd_step(want_info=True)
+            toks.append(tok)
+            infos.append((info.matched, info.match_idx, tuple(info.cand[:k])))
+            zs.append(P.ppd_get_logits().copy())
+            es.append(P.ppd_get_early_logits().copy())
+        st = P.ppd_get_stats()
+        P.close()
+        return toks, np.stack(zs), np.stack(es), infos, st
+
+    t1, z1, e1, i1, st1 = run()
+    monkeypatch.setenv("PPD_SPEC", "2")
+    t0, z0, e0, i0, st0 = run()
+    monkeypatch.delenv("PPD_SPEC")
+    assert t1 == t0 and i1 == i0
+    np.testing.assert_array_equal(z1.view(np.uint32), z0.view(np.uint32))
+    np.testing.assert_array_equal(e1.view(np.uint32), e0.view(np.uint32))
+    assert st1["matches"] == st0["matches"] and st1["main_layer_rows"] == st0["main_layer_rows"]
+    if cfg.wdtype == pi.WD_BF16:
+        # rounds that follow a match (not the one after the plain step, not past the end) skipped their early head
+        hits = [m for m, _, _ in i1]
+        follow = sum(1 for j in range(1, len(hits)) if hits[j - 1] and j != cfg.n_gen // 2)
+        head_bytes = cfg.vocab * cfg.d_model * cfg.wbytes
+        assert st0["weight_bytes"] - st1["weight_bytes"] == follow * head_bytes
+        assert follow > 0
