@@ -76,8 +76,19 @@ def _load():
         lib.orc_topk.restype = None
         lib.orc_argmax.argtypes = [vp, ci]
         lib.orc_argmax.restype = ci
+        lib.orc_set_selection.argtypes = [vp, ci, ci, ctypes.c_double, ctypes.c_uint64]
+        lib.orc_set_selection.restype = None
+        lib.orc_philox4x32_10.argtypes = [vp, vp, vp]
+        lib.orc_philox4x32_10.restype = None
+        lib.orc_uniform.argtypes = [ctypes.c_uint64, ctypes.c_int64]
+        lib.orc_uniform.restype = ctypes.c_double
+        lib.orc_sample.argtypes = [vp, ci, ci, ci, ctypes.c_double, ctypes.c_double]
+        lib.orc_sample.restype = ci
         _lib = lib
     return _lib
+
+
+GREEDY, TOP_K, TOP_P = 0, 1, 2
 
 
 def _ptr(a: Optional[np.ndarray]):
@@ -123,6 +134,11 @@ class Oracle:
             pass
 
     # -- decoding ---------------------------------------------------------
+    def set_selection(self, mode=GREEDY, top_k=0, top_p=1.0, seed=0):
+        """Rule for the final prediction of every decoding loop of this object (Appendix B):
+        GREEDY, TOP_K sampling or TOP_P sampling with the counter-based uniform of (seed, position)."""
+        _load().orc_set_selection(self._h, int(mode), int(top_k), float(top_p), int(seed))
+
     def plain_greedy(self, prompt, ell, want_logits=False, eos=-1):
         prompt = np.ascontiguousarray(prompt, dtype=np.int32)
         toks = np.zeros(ell, dtype=np.int32)
@@ -206,3 +222,22 @@ def topk(z, k):
 def argmax(z):
     z = np.ascontiguousarray(z, dtype=np.float64)
     return int(_load().orc_argmax(z.ctypes.data, len(z)))
+
+
+def philox4x32_10(ctr, key):
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    _load().orc_philox4x32_10(c.ctypes.data, k.ctypes.data, out.ctypes.data)
+    return out
+
+
+def uniform(seed: int, index: int) -> float:
+    """u in [0, 1) of the token chosen at sequence position ``index``."""
+    return float(_load().orc_uniform(int(seed), int(index)))
+
+
+def sample(z, mode, top_k, top_p, u):
+    """Token drawn from the truncated softmax of the logits z by inversion at u."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    return int(_load().orc_sample(z.ctypes.data, len(z), int(mode), int(top_k), float(top_p), float(u)))

@@ -22,13 +22,22 @@
  *     1..d-dbar on its candidate, verification and adoption.
  *   - the per-sequence counters of Sec. 4.2 (main-process layer executions =
  *     latency in time units, sub-process layer executions, number of runs N).
+ *   - the sampling-based variants of Appendix B: the final prediction is drawn
+ *     by top-k sampling or top-p (nucleus) sampling instead of the arg max;
+ *     everything else of the loop is unchanged.  The random number of a step
+ *     is a counter-based one (Philox-4x32-10, Salmon et al., SC 2011) of
+ *     (seed, position of the token being chosen), so that decoding with and
+ *     without PPD draw the same numbers.
  *
  * Readings where the paper is silent are listed next to the code that takes
  * them.  Parity pins: tests/test_oracle_*.py.
  *
  * Pin status: forward numerics are pinned sub-op by sub-op and end to end
  * against library routines (torch CPU fp64) and closed forms; the control
- * loop by the paper's exactness invariant and counter identities.
+ * loop by the paper's exactness invariant and counter identities; the
+ * generator by the known-answer vectors of its reference distribution, the
+ * samplers by closed forms (two-token cases, uniform logits, k = 1, p -> 0)
+ * and by exact inversion against a library softmax.
  */
 #include <math.h>
 #include <stdint.h>
@@ -67,6 +76,10 @@ typedef struct orc_model {
   int ctx_cap;
   double *K, *V;         /* [n_layers][ctx_cap][d_model] */
   double *tailK, *tailV; /* [n_layers][ORC_KMAX][d_model]: one slot per sub-process */
+  /* rule for the final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling */
+  int sel_mode, sel_k;
+  double sel_p;
+  uint64_t sel_seed;
 } orc_model;
 
 /* ------------------------------------------------------------------ helpers */
@@ -267,7 +280,80 @@ static void topk_ids(const double *z, int n, int k, int32_t *ids) {
   }
 }
 
+/* ---- sampling-based final prediction (Appendix B)
+ *
+ * Philox-4x32-10: ten rounds of two 32x32->64 multiplications whose high and
+ * low halves are crossed over and mixed with the counter words and the key;
+ * the key moves on by the Weyl constants between rounds. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint64_t a = (uint64_t)0xD2511F53u * c0, b = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0, n1 = (uint32_t)b;
+    const uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1, n3 = (uint32_t)a;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* u in [0, 1) for the token chosen at sequence position `index`: the top 24
+ * bits of the first output word (exact in fp32 and fp64 alike). */
+double orc_uniform(uint64_t seed, int64_t index) {
+  const uint32_t ctr[4] = {(uint32_t)((uint64_t)index & 0xffffffffu), (uint32_t)((uint64_t)index >> 32), 0u, 0u};
+  const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+  uint32_t out[4];
+  orc_philox4x32_10(ctr, key, out);
+  return (double)(out[0] >> 8) / 16777216.0;
+}
+
+typedef struct { double z; int id; } orc_zi;
+static int by_logit_desc(const void *a, const void *b) {
+  const orc_zi *x = (const orc_zi *)a, *y = (const orc_zi *)b;
+  if (x->z != y->z) return x->z > y->z ? -1 : 1;
+  return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);
+}
+
+/* Draw from the truncated softmax by inversion.  Tokens are ranked by
+ * (logit descending, id ascending); w_j = exp(z_j - z_max).
+ *   mode 1, top-k sampling (Fan et al. 2018): the ks most probable tokens are kept;
+ *   mode 2, top-p sampling (Holtzman et al. 2019): the shortest prefix of the
+ *           ranking whose probability mass reaches p is kept.
+ * With W the kept mass, the token is the first of the ranking whose cumulative
+ * mass exceeds u W.  mode 0 is the arg max. */
+int orc_sample(const double *z, int n, int mode, int ks, double p, double u) {
+  if (mode == 0) return argmax_first(z, n);
+  orc_zi *r = (orc_zi *)malloc(sizeof(orc_zi) * (size_t)n);
+  for (int i = 0; i < n; ++i) { r[i].z = z[i]; r[i].id = i; }
+  qsort(r, (size_t)n, sizeof(orc_zi), by_logit_desc);
+  double *cum = (double *)malloc(sizeof(double) * (size_t)n);
+  double acc = 0.0;
+  for (int j = 0; j < n; ++j) { acc += exp(r[j].z - r[0].z); cum[j] = acc; }
+  int keep;
+  if (mode == 1) keep = ks < n ? (ks < 1 ? 1 : ks) : n;
+  else {
+    keep = n;
+    for (int j = 0; j < n; ++j) if (cum[j] >= p * cum[n - 1]) { keep = j + 1; break; }
+  }
+  const double target = u * cum[keep - 1];
+  int pick = keep - 1;
+  for (int j = 0; j < keep; ++j) if (cum[j] > target) { pick = j; break; }
+  const int id = r[pick].id;
+  free(r); free(cum);
+  return id;
+}
+
+/* The final prediction of the token that will sit at sequence position `index`. */
+static int select_final(const orc_model *m, const double *z, int64_t index) {
+  if (m->sel_mode == 0) return argmax_first(z, m->d.vocab);
+  return orc_sample(z, m->d.vocab, m->sel_mode, m->sel_k, m->sel_p, orc_uniform(m->sel_seed, index));
+}
+
 /* ------------------------------------------------------------------ C API */
+
+void orc_set_selection(orc_model *m, int mode, int ks, double p, uint64_t seed) {
+  m->sel_mode = mode; m->sel_k = ks; m->sel_p = p; m->sel_seed = seed;
+}
 
 orc_model *orc_create(const orc_dims *d, const orc_weights *w, int ctx_cap) {
   orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
@@ -315,7 +401,7 @@ int orc_plain_greedy(orc_model *m, const int32_t *prompt, int P, int ell, int eo
     embed(m, x, pos, h);
     for (int l = 0; l < d; ++l) block_forward(m, l, h, pos, cacheK(m, l, pos), cacheV(m, l, pos));
     head_logits(m, h, 0, z);
-    x = argmax_first(z, V);
+    x = select_final(m, z, pos + 1);
     tokens_out[t] = x;
     if (logits_out) memcpy(logits_out + (size_t)t * V, z, sizeof(double) * V);
     ++pos; ++t;
@@ -393,7 +479,7 @@ int orc_plain_recompute(orc_model *m, const int32_t *prompt, int P, int ell, int
     int n = P + t;
     orc_full_forward(m, seq, n, z);
     const double *last = z + (size_t)(n - 1) * V;
-    int x = argmax_first(last, V);
+    int x = select_final(m, last, n);
     seq[n] = x;
     tokens_out[t] = x;
     if (logits_out) memcpy(logits_out + (size_t)t * V, last, sizeof(double) * V);
@@ -455,7 +541,7 @@ int orc_ppd(orc_model *m, const int32_t *prompt, int P, int ell, int k, int dbar
     for (int l = dbar; l < d; ++l) block_forward(m, l, hm, pos, cacheK(m, l, pos), cacheV(m, l, pos));
     st.main_layer_rows += d - dbar;
     head_logits(m, hm, 0, zf);
-    int xn = argmax_first(zf, V);
+    int xn = select_final(m, zf, pos + 1);
     for (int i = 0; i < k; ++i) {
       double *hi = hs + (size_t)i * dm;
       embed(m, cand[i], pos + 1, hi);
