@@ -160,6 +160,20 @@ int ppd_step(ppd_ctx *ctx, int32_t *out_tokens, int max_out, ppd_step_info *info
  * mixed with ppd_step on one context: a pending match is dropped. */
 int plain_greedy_step(ppd_ctx *ctx, int32_t *out_token);
 
+/* Rule for the final prediction (Appendix B: sampling-based decoding uses PPD
+ * unchanged except that the final prediction is drawn by top-k or top-p
+ * sampling instead of the arg max).  mode 0: arg max (default); 1: top-k
+ * sampling, the top_k most probable tokens kept; 2: top-p sampling, the
+ * shortest prefix of the ranking by probability whose mass reaches top_p kept.
+ * The token is drawn by inversion from the renormalised kept softmax of the
+ * final fp32 logits, in fp64, tokens ranked by (logit descending, id
+ * ascending); the uniform number of a step is the top 24 bits of the first
+ * word of Philox-4x32-10 with key = seed and counter = sequence position of
+ * the token being chosen, so ppd_step and plain_greedy_step draw the same
+ * tokens.  Applies to both kinds of step from the next call on.  PPD_EINVAL
+ * for an unknown mode, top_k < 1 (mode 1), top_p outside (0, 1] (mode 2). */
+int ppd_set_sampling(ppd_ctx *ctx, int mode, int top_k, double top_p, uint64_t seed);
+
 /* Test hooks.  host_logits: HOST float[vocab].  Final-layer logits of the last
  * ppd_step / plain_greedy_step, and early-exit logits of the last ppd_step. */
 int ppd_get_logits(ppd_ctx *ctx, float *host_logits);

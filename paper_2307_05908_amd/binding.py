@@ -50,7 +50,7 @@ class Stats(ctypes.Structure):
 
 
 EXPORTS = ("ppd_create", "ppd_reset", "ppd_prefill", "ppd_step", "plain_greedy_step", "ppd_get_logits",
-           "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_set_graphs", "ppd_get_kernel_time",
+           "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_set_graphs", "ppd_set_sampling", "ppd_get_kernel_time",
            "ppd_time_ffn_in", "ppd_stream_read_probe", "ppd_destroy",
            "ppd_strerror", "ppd_last_hip_error")
 
@@ -80,6 +80,7 @@ def load_library() -> ctypes.CDLL:
     lib.ppd_get_stats.argtypes = [vp, ctypes.POINTER(Stats)]
     lib.ppd_set_profiling.argtypes = [vp, ci]
     lib.ppd_set_graphs.argtypes = [vp, ci]
+    lib.ppd_set_sampling.argtypes = [vp, ci, ci, ctypes.c_double, ctypes.c_uint64]
     lib.ppd_get_kernel_time.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
     lib.ppd_time_ffn_in.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_stream_read_probe.argtypes = [vp, ctypes.c_uint64, ci, ctypes.POINTER(ctypes.c_double)]
@@ -215,6 +216,10 @@ class PPD:
 
     def ppd_set_graphs(self, on: bool):
         self._chk(load_library().ppd_set_graphs(self._h, int(on)), "ppd_set_graphs")
+
+    def ppd_set_sampling(self, mode: int, top_k: int = 0, top_p: float = 1.0, seed: int = 0):
+        """Final prediction by arg max (0), top-k sampling (1) or top-p sampling (2)."""
+        self._chk(load_library().ppd_set_sampling(self._h, int(mode), int(top_k), float(top_p), int(seed)), "ppd_set_sampling")
 
     def ppd_time_ffn_in(self, reps: int = 64) -> float:
         """Average milliseconds per FFN-in GEMM launch in a back-to-back burst (invalidates the sequence)."""

@@ -63,6 +63,9 @@ struct ppd_ctx {
   // next round (kind 3) starts with its parallel phase: one head pass per matching round instead of two.
   int spec;
   int last_kind;
+  // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
+  int samp_mode, samp_k; double samp_p; uint64_t samp_seed;
+  double* samp_w;                // [vocab] scratch of the sampling kernel
   int head_grid;
   float2 *rope;          // [max_ctx][hd/2]
   DevState *ds;
@@ -457,7 +460,16 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     } else
     HIPCHK(c, launch_gemm(c, a, 1, false));
   }
+  if (!early && c->samp_mode) {
+    SampleArgs sa; memset(&sa, 0, sizeof sa);
+    sa.z = c->logits; sa.n = d.vocab; sa.mode = c->samp_mode; sa.ks = c->samp_k; sa.p = c->samp_p; sa.seed = c->samp_seed;
+    sa.ds = c->ds; sa.w = c->samp_w;
+    ProfScope ps(c, PPD_KC_SELECT);
+    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(SAMP_THREADS), 0, c->cur, sa);
+    HIPCHK(c, hipGetLastError());
+  }
   SelectArgs s; memset(&s, 0, sizeof s);
+  s.sampled = (!early && c->samp_mode) ? 1 : 0;
   s.pk_val = c->pk_val; s.pk_idx = c->pk_idx; s.nblk = c->head_grid; s.kk = (early || spec) ? c->k : 1;
   s.pk_stride = (int)c->pk_slots;
   s.k = adopt || early ? c->k : 0; s.mode = early ? 0 : 1; s.ds = c->ds; s.host_result = c->host_result_dev;
@@ -603,7 +615,7 @@ void account_round(ppd_ctx* c, int kind, int pos) {
 void free_all(ppd_ctx* c) {
   for (int i = 0; i < 4; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
-                 c->early_logits, c->early_spec, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
+                 c->early_logits, c->early_spec, c->samp_w, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
@@ -699,6 +711,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   alloc((void**)&c->part, R * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
   alloc((void**)&c->logits, R * d.vocab * sizeof(float));
   alloc((void**)&c->early_spec, (size_t)2 * d.vocab * sizeof(float));
+  alloc((void**)&c->samp_w, (size_t)d.vocab * sizeof(double));
   alloc((void**)&c->early_logits, (size_t)d.vocab * sizeof(float));
   const size_t pk_slots = (size_t)(c->head_grid > (d.vocab + 255) / 256 ? c->head_grid : (d.vocab + 255) / 256) + 1024;   // room for either head grid
   c->pk_slots = pk_slots;
@@ -912,6 +925,18 @@ int ppd_set_profiling(ppd_ctx* c, int on) {
   c->prof = on < 0 ? 0 : (on > 2 ? 2 : on);
   c->ev_used = 0;
   if (on) { memset(c->kc_ms, 0, sizeof c->kc_ms); memset(c->kc_n, 0, sizeof c->kc_n); }
+  return PPD_OK;
+}
+
+int ppd_set_sampling(ppd_ctx* c, int mode, int top_k, double top_p, uint64_t seed) {
+  if (!c || mode < 0 || mode > 2) return PPD_EINVAL;
+  if (mode == 1 && top_k < 1) return PPD_EINVAL;
+  if (mode == 2 && !(top_p > 0.0 && top_p <= 1.0)) return PPD_EINVAL;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->samp_mode = mode; c->samp_k = top_k; c->samp_p = top_p; c->samp_seed = seed;
+  // the captured rounds hold the old rule
+  for (int i = 0; i < 4; ++i)
+    if (c->graph[i]) { HIPCHK(c, hipGraphExecDestroy(c->graph[i])); c->graph[i] = nullptr; }
   return PPD_OK;
 }
 

@@ -45,6 +45,7 @@ struct DevState {
   int32_t result[2];  // token x_{t+1}, match_idx of the last final selection
   int32_t cand[MAXM]; // early top-k ids
   int32_t cand_next[MAXM]; // candidates of the next round, predicted at the end of a matching round
+  int32_t sampled;    // final prediction drawn by the sampling kernel (sampling-based variants)
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
@@ -868,7 +869,214 @@ struct SelectArgs {
   float* early_spec;        // [2][vocab]: the matching row's logits are kept as the early logits of the round at
                             // the next position, in the half that position's parity selects
   int vocab;
+  int sampled;              // mode 1: the final prediction is ds->sampled (drawn by sample_kernel), not the arg max
 };
+// ------------------------------------------------------------------ sampling-based final prediction
+// Appendix B: the final prediction is drawn by top-k or top-p sampling instead of the arg max; the rest of a
+// round is unchanged.  One workgroup draws the token by inversion from the fp32 logits, in fp64: tokens are
+// ranked by (logit descending, id ascending), w_i = exp(z_i - z_max); top-k sampling keeps the ks first of the
+// ranking, top-p the shortest prefix whose mass reaches p times the total; with W the kept mass, the token is
+// the first of the ranking whose cumulative mass exceeds u W.  u comes from Philox-4x32-10 (Salmon et al.,
+// SC 2011) keyed by the seed, counter = sequence position of the token being chosen: decoding with and
+// without PPD draws the same numbers.
+// No sort: each of the two questions ("where does the kept prefix end", "where does the cumulative mass pass
+// u W") asks for the largest key whose mass-at-or-above meets a bound, found digit by digit (eight passes of
+// four bits over an order-preserving 32-bit image of the logit, sixteen bins per pass, fixed-order sums).
+#ifdef PPD_ENGINE_TU
+constexpr int SAMP_THREADS = 1024;
+struct SampleArgs {
+  const float* z; int n;     // logits [n]
+  int mode, ks;              // 1 top-k sampling (ks kept), 2 top-p sampling
+  double p;
+  uint64_t seed;
+  DevState* ds;              // reads pos, writes sampled
+  double* w;                 // scratch [n]
+};
+
+__device__ inline uint32_t samp_key(float z) {        // larger logit <-> larger key; -0 and +0 are one value
+  const uint32_t b = __float_as_uint(z == 0.f ? 0.f : z);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ inline float samp_unkey(uint32_t k) { return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k); }
+
+// ten rounds: two 32x32->64 products, halves crossed over and mixed with counter and key; key steps by the Weyl constants
+__device__ inline uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+  for (int r = 0; r < 10; ++r) {
+    if (r) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+    c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+  }
+  return c0;
+}
+
+__global__ __launch_bounds__(SAMP_THREADS) void sample_kernel(SampleArgs a) {
+  constexpr int NW = SAMP_THREADS / WAVE;
+  __shared__ double s_bd[NW][16];
+  __shared__ int s_bc[NW][16];
+  __shared__ double s_tot[16];
+  __shared__ int s_cnt[16];
+  __shared__ double s_red[NW];
+  __shared__ float s_redf[NW];
+  __shared__ uint32_t s_prefix; __shared__ double s_above; __shared__ int s_nabove, s_ties, s_r, s_min;
+  __shared__ double s_W;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = a.n;
+  auto xsum = [&](double v) { for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o); return v; };
+  auto xsumi = [&](int v) { for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o); return v; };
+
+  // ---- largest logit, weights, total mass
+  float mx = -INFINITY;
+  for (int i = tid; i < n; i += SAMP_THREADS) mx = fmaxf(mx, a.z[i]);
+  for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if (lane == 0) s_redf[wave] = mx;
+  __syncthreads();
+  mx = s_redf[0];
+  for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_redf[w]);
+  const double zmax = (double)mx;
+  double part = 0.0;
+  for (int i = tid; i < n; i += SAMP_THREADS) {
+    const double w = exp((double)a.z[i] - zmax);
+    a.w[i] = w;
+    part += w;
+  }
+  part = xsum(part);
+  if (lane == 0) s_red[wave] = part;
+  __syncthreads();
+  double S = 0.0;
+  for (int w = 0; w < NW; ++w) S += s_red[w];
+
+  // ---- the largest key kappa whose mass at or above it meets the bound.  kind 0: mass >= T; 1: mass > T;
+  // 2: count >= K.  Leaves s_prefix = kappa, s_above / s_nabove = mass / count strictly above, s_ties = tokens at kappa.
+  auto search = [&](int kind, double T, int K) {
+    __syncthreads();
+    if (tid == 0) { s_prefix = 0u; s_above = 0.0; s_nabove = 0; }
+    for (int shift = 28; shift >= 0; shift -= 4) {
+      __syncthreads();
+      const uint32_t prefix = s_prefix;
+      double acc[16]; int cn[16];
+#pragma unroll
+      for (int b = 0; b < 16; ++b) { acc[b] = 0.0; cn[b] = 0; }
+      for (int i = tid; i < n; i += SAMP_THREADS) {
+        const uint32_t k = samp_key(a.z[i]);
+        const bool in = shift == 28 || (k >> (shift + 4)) == prefix;
+        if (in) {
+          const int nib = (k >> shift) & 15;
+          const double w = a.w[i];
+#pragma unroll
+          for (int b = 0; b < 16; ++b) { acc[b] += nib == b ? w : 0.0; cn[b] += nib == b ? 1 : 0; }
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < 16; ++b) {
+        const double v = xsum(acc[b]); const int c = xsumi(cn[b]);
+        if (lane == 0) { s_bd[wave][b] = v; s_bc[wave][b] = c; }
+      }
+      __syncthreads();
+      if (tid < 16) {
+        double v = 0.0; int c = 0;
+        for (int w = 0; w < NW; ++w) { v += s_bd[w][tid]; c += s_bc[w][tid]; }
+        s_tot[tid] = v; s_cnt[tid] = c;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        double g = s_above; int c = s_nabove, pick = -1;
+        for (int b = 15; b >= 0; --b) {
+          if (s_cnt[b] == 0) continue;
+          const double g2 = g + s_tot[b]; const int c2 = c + s_cnt[b];
+          const bool ok = kind == 0 ? g2 >= T : (kind == 1 ? g2 > T : c2 >= K);
+          // the lowest occupied digit is taken when rounding leaves the bound just unmet everywhere
+          bool last = true;
+          for (int q = b - 1; q >= 0; --q) last = last && s_cnt[q] == 0;
+          if (ok || last) { pick = b; break; }
+          g = g2; c = c2;
+        }
+        if (pick < 0) pick = 0;      // (cannot happen: the digit picked in the pass before was occupied)
+        s_above = g; s_nabove = c; s_prefix = (prefix << 4) | (uint32_t)pick; s_ties = s_cnt[pick];
+      }
+    }
+    __syncthreads();
+  };
+
+  // ---- kept mass W
+  const int pos_new = a.ds->pos + 1;
+  const uint32_t word = philox4x32_10_word0((uint32_t)pos_new, 0u, 0u, 0u, (uint32_t)(a.seed & 0xffffffffu), (uint32_t)(a.seed >> 32));
+  const double u = (double)(word >> 8) * (1.0 / 16777216.0);
+  if (a.mode == 1) {
+    int ks = a.ks < 1 ? 1 : a.ks;
+    if (ks >= n) { if (tid == 0) s_W = S; }
+    else {
+      search(2, 0.0, ks);
+      if (tid == 0) {
+        const double wk = exp((double)samp_unkey(s_prefix) - zmax);
+        double W = s_above;
+        for (int r = s_nabove; r < ks; ++r) W += wk;
+        s_W = W;
+      }
+    }
+  } else {
+    const double T = a.p * S;
+    search(0, T, 0);
+    if (tid == 0) {
+      const double wk = exp((double)samp_unkey(s_prefix) - zmax);
+      double W = s_above; int r = 0;
+      do { W += wk; ++r; } while (W < T && r < s_ties);
+      s_W = W;
+    }
+  }
+  __syncthreads();
+  // ---- the first token of the ranking whose cumulative mass exceeds u W
+  const double t = u * s_W;
+  search(1, t, 0);
+  const uint32_t kappa = s_prefix;
+  if (tid == 0) {
+    const double wk = exp((double)samp_unkey(kappa) - zmax);
+    double c = s_above; int r = 0;
+    do { c += wk; ++r; } while (!(c > t) && r < s_ties);
+    s_r = r;                       // the r-th smallest id among the tokens at kappa
+    s_min = 0x7fffffff;
+  }
+  __syncthreads();
+  const int r = s_r;
+  if (r == 1) {
+    for (int i = tid; i < n; i += SAMP_THREADS)
+      if (samp_key(a.z[i]) == kappa) atomicMin(&s_min, i);
+    __syncthreads();
+    if (tid == 0) a.ds->sampled = s_min;
+    return;
+  }
+  // several tokens share the logit: the r-th smallest id among them, again digit by digit (counts, ascending)
+  if (tid == 0) { s_prefix = 0u; s_nabove = r; }
+  for (int shift = 28; shift >= 0; shift -= 4) {
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    int cn[16];
+#pragma unroll
+    for (int b = 0; b < 16; ++b) cn[b] = 0;
+    for (int i = tid; i < n; i += SAMP_THREADS) {
+      const bool in = samp_key(a.z[i]) == kappa && (shift == 28 || ((uint32_t)i >> (shift + 4)) == prefix);
+      if (in) {
+        const int nib = ((uint32_t)i >> shift) & 15;
+#pragma unroll
+        for (int b = 0; b < 16; ++b) cn[b] += nib == b ? 1 : 0;
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < 16; ++b) { const int c = xsumi(cn[b]); if (lane == 0) s_bc[wave][b] = c; }
+    __syncthreads();
+    if (tid < 16) { int c = 0; for (int w = 0; w < NW; ++w) c += s_bc[w][tid]; s_cnt[tid] = c; }
+    __syncthreads();
+    if (tid == 0) {
+      int need = s_nabove, pick = 15;
+      for (int b = 0; b < 16; ++b) { if (s_cnt[b] >= need) { pick = b; break; } need -= s_cnt[b]; }
+      s_nabove = need; s_prefix = (prefix << 4) | (uint32_t)pick;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) a.ds->sampled = (int32_t)s_prefix;
+}
+#endif
+
 constexpr int SEL_THREADS = 256;
 
 // every workgroup merges the block candidates redundantly (they are few); winners land in win[]
@@ -938,7 +1146,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
     return;
   }
   // final: verification
-  const int token = win[0];
+  const int token = a.sampled ? a.ds->sampled : win[0];
   if (tid == 0) {
     int midx = -1;
     for (int q = 0; q < a.k; ++q) if (a.ds->cand[q] == token) { midx = q; break; }
