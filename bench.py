@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--exit-layer", type=int, default=None)
     ap.add_argument("--prompt", type=int, default=None)
+    ap.add_argument("--sampling", choices=["greedy", "topk", "topp"], default="greedy",
+                    help="final prediction: arg max (the headline), top-k sampling (3 kept) or top-p sampling (0.95), Appendix B")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=32)
     ap.add_argument("--copy-probe", action="store_true",
@@ -96,6 +98,8 @@ def main():
 
     # ---- PPD rounds (each call is synchronous: the host clock around a call is the round's latency)
     P = binding.PPD(cfg, dev, k=k, exit_layer=e)
+    if args.sampling != "greedy":
+        P.ppd_set_sampling(1 if args.sampling == "topk" else 2, 3, 0.95, 1234)
     round_ms, round_hit = [], []
 
     def ppd_round():
@@ -198,7 +202,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if cfg.wdtype == pi.WD_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {d} layers, d_model {cfg.d_model}, d_ff {cfg.d_ff}, vocab {cfg.vocab}, "
                                f"batch 1, prompt {n_prompt} uniform-random ids, random-init N(0,0.02) weights",
-                   "k": k, "exit_layer": e, "alpha": cfg.alpha},
+                   "k": k, "exit_layer": e, "alpha": cfg.alpha,
+                   "final_prediction": {"greedy": "arg max", "topk": "top-k sampling, 3 kept", "topp": "top-p sampling, p = 0.95"}[args.sampling]},
         "round_ms": {"mean": round(float(round_ms.mean()), 4), "p50": round(float(np.percentile(round_ms, 50)), 4),
                      "p95": round(float(np.percentile(round_ms, 95)), 4),
                      "after_hit_mean": round(float(round_ms[after_hit].mean()), 4) if after_hit.any() else None,

@@ -65,7 +65,7 @@ struct ppd_ctx {
   int last_kind;
   // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
   int samp_mode, samp_k; double samp_p; uint64_t samp_seed;
-  double* samp_w;                // [vocab] scratch of the sampling kernel
+  double* samp_w; uint32_t* samp_keys; int samp_npad;   // scratch of the sampling kernel
   int head_grid;
   float2 *rope;          // [max_ctx][hd/2]
   DevState *ds;
@@ -463,9 +463,10 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
   if (!early && c->samp_mode) {
     SampleArgs sa; memset(&sa, 0, sizeof sa);
     sa.z = c->logits; sa.n = d.vocab; sa.mode = c->samp_mode; sa.ks = c->samp_k; sa.p = c->samp_p; sa.seed = c->samp_seed;
-    sa.ds = c->ds; sa.w = c->samp_w;
+    sa.ds = c->ds; sa.w = c->samp_w; sa.keys = c->samp_keys; sa.npad = c->samp_npad;
     ProfScope ps(c, PPD_KC_SELECT);
-    hipLaunchKernelGGL(sample_kernel, dim3(1), dim3(SAMP_THREADS), 0, c->cur, sa);
+    if (d.vocab <= SAMP_VPT * SAMP_THREADS) hipLaunchKernelGGL(sample_kernel<true>, dim3(1), dim3(SAMP_THREADS), 0, c->cur, sa);
+    else hipLaunchKernelGGL(sample_kernel<false>, dim3(1), dim3(SAMP_THREADS), 0, c->cur, sa);
     HIPCHK(c, hipGetLastError());
   }
   SelectArgs s; memset(&s, 0, sizeof s);
@@ -615,7 +616,7 @@ void account_round(ppd_ctx* c, int kind, int pos) {
 void free_all(ppd_ctx* c) {
   for (int i = 0; i < 4; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
-                 c->early_logits, c->early_spec, c->samp_w, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
+                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
@@ -711,7 +712,9 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   alloc((void**)&c->part, R * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
   alloc((void**)&c->logits, R * d.vocab * sizeof(float));
   alloc((void**)&c->early_spec, (size_t)2 * d.vocab * sizeof(float));
-  alloc((void**)&c->samp_w, (size_t)d.vocab * sizeof(double));
+  c->samp_npad = (d.vocab + SAMP_THREADS * SAMP_MEMU - 1) / (SAMP_THREADS * SAMP_MEMU) * (SAMP_THREADS * SAMP_MEMU);
+  alloc((void**)&c->samp_w, (size_t)c->samp_npad * sizeof(double));
+  alloc((void**)&c->samp_keys, (size_t)c->samp_npad * sizeof(uint32_t));
   alloc((void**)&c->early_logits, (size_t)d.vocab * sizeof(float));
   const size_t pk_slots = (size_t)(c->head_grid > (d.vocab + 255) / 256 ? c->head_grid : (d.vocab + 255) / 256) + 1024;   // room for either head grid
   c->pk_slots = pk_slots;

@@ -880,20 +880,26 @@ struct SelectArgs {
 // SC 2011) keyed by the seed, counter = sequence position of the token being chosen: decoding with and
 // without PPD draws the same numbers.
 // No sort: each of the two questions ("where does the kept prefix end", "where does the cumulative mass pass
-// u W") asks for the largest key whose mass-at-or-above meets a bound, found digit by digit (eight passes of
-// four bits over an order-preserving 32-bit image of the logit, sixteen bins per pass, fixed-order sums).
+// u W") asks for the largest key kappa whose mass-at-or-above G(kappa) meets a bound; G is evaluated in full, in
+// one fixed order of additions, for one trial key per pass (so it is monotone in the key whatever the rounding),
+// and kappa is fixed bit by bit from the top of an order-preserving 32-bit image of the logit.
 #ifdef PPD_ENGINE_TU
 constexpr int SAMP_THREADS = 1024;
+constexpr int SAMP_MEMU = 8;     // loads in flight per thread when the logits are re-read from memory
+constexpr int SAMP_VPT = 32;     // logits per thread kept on chip (weights in registers, keys in LDS): vocabularies up to 32768;
+                                 // larger ones re-read memory every pass
 struct SampleArgs {
   const float* z; int n;     // logits [n]
   int mode, ks;              // 1 top-k sampling (ks kept), 2 top-p sampling
   double p;
   uint64_t seed;
   DevState* ds;              // reads pos, writes sampled
-  double* w;                 // scratch [n]
+  double* w; uint32_t* keys; // scratch [npad] each (only used when the logits do not fit the chip): weights and keys,
+  int npad;                  // zero beyond n; npad = n rounded up to a multiple of SAMP_THREADS * SAMP_MEMU
 };
 
-__device__ inline uint32_t samp_key(float z) {        // larger logit <-> larger key; -0 and +0 are one value
+// larger logit <-> larger key; -0 and +0 are one value; no finite or infinite logit has key 0
+__device__ inline uint32_t samp_key(float z) {
   const uint32_t b = __float_as_uint(z == 0.f ? 0.f : z);
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
@@ -911,142 +917,171 @@ __device__ inline uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_
   return c0;
 }
 
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double v) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)b, CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xf, 0xf, false);
+  return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+__device__ __forceinline__ double lane_f64(double v, int l) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_readlane((int)b, l), hi = __builtin_amdgcn_readlane((int)(b >> 32), l);
+  return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+__device__ __forceinline__ double wave_sum_f64(double v) {     // same scheme as wave_sum
+  v += dpp_f64<0xB1>(v);
+  v += dpp_f64<0x4E>(v);
+  v += dpp_f64<0x141>(v);
+  v += dpp_f64<0x140>(v);
+  return ((lane_f64(v, 0) + lane_f64(v, 16)) + lane_f64(v, 32)) + lane_f64(v, 48);
+}
+
+template <bool REG>
 __global__ __launch_bounds__(SAMP_THREADS) void sample_kernel(SampleArgs a) {
   constexpr int NW = SAMP_THREADS / WAVE;
-  __shared__ double s_bd[NW][16];
-  __shared__ int s_bc[NW][16];
-  __shared__ double s_tot[16];
-  __shared__ int s_cnt[16];
-  __shared__ double s_red[NW];
+  constexpr int VPT = REG ? SAMP_VPT : 1;
+  __shared__ double s_m[2][NW];
+  __shared__ int s_c[2][NW];
   __shared__ float s_redf[NW];
-  __shared__ uint32_t s_prefix; __shared__ double s_above; __shared__ int s_nabove, s_ties, s_r, s_min;
-  __shared__ double s_W;
+  __shared__ int s_bc[NW][16];
+  __shared__ int s_cnt[16];
+  __shared__ uint32_t s_prefix; __shared__ int s_need, s_min;
+  __shared__ uint32_t s_key[REG ? SAMP_VPT * SAMP_THREADS : 1];     // key of token tid + e * SAMP_THREADS at [e][tid]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = a.n;
-  auto xsum = [&](double v) { for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o); return v; };
-  auto xsumi = [&](int v) { for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o); return v; };
+  uint32_t* const key = s_key + tid;
+  constexpr int KS = SAMP_THREADS;     // stride between a thread's keys
 
-  // ---- largest logit, weights, total mass
+  // ---- keys, largest logit, weights
+  double wr[VPT];
   float mx = -INFINITY;
-  for (int i = tid; i < n; i += SAMP_THREADS) mx = fmaxf(mx, a.z[i]);
-  for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if (REG) {
+#pragma unroll
+    for (int e = 0; e < VPT; ++e) {
+      const int i = tid + e * SAMP_THREADS;
+      uint32_t k = 0u;
+      if (i < n) { const float z = a.z[i]; k = samp_key(z); mx = fmaxf(mx, z); }
+      key[e * KS] = k;
+    }
+  } else {
+    for (int i = tid; i < n; i += SAMP_THREADS) mx = fmaxf(mx, a.z[i]);
+  }
+  mx = wave_max(mx);
   if (lane == 0) s_redf[wave] = mx;
   __syncthreads();
   mx = s_redf[0];
   for (int w = 1; w < NW; ++w) mx = fmaxf(mx, s_redf[w]);
   const double zmax = (double)mx;
-  double part = 0.0;
-  for (int i = tid; i < n; i += SAMP_THREADS) {
-    const double w = exp((double)a.z[i] - zmax);
-    a.w[i] = w;
-    part += w;
-  }
-  part = xsum(part);
-  if (lane == 0) s_red[wave] = part;
-  __syncthreads();
-  double S = 0.0;
-  for (int w = 0; w < NW; ++w) S += s_red[w];
-
-  // ---- the largest key kappa whose mass at or above it meets the bound.  kind 0: mass >= T; 1: mass > T;
-  // 2: count >= K.  Leaves s_prefix = kappa, s_above / s_nabove = mass / count strictly above, s_ties = tokens at kappa.
-  auto search = [&](int kind, double T, int K) {
-    __syncthreads();
-    if (tid == 0) { s_prefix = 0u; s_above = 0.0; s_nabove = 0; }
-    for (int shift = 28; shift >= 0; shift -= 4) {
-      __syncthreads();
-      const uint32_t prefix = s_prefix;
-      double acc[16]; int cn[16];
+  if (REG) {
 #pragma unroll
-      for (int b = 0; b < 16; ++b) { acc[b] = 0.0; cn[b] = 0; }
-      for (int i = tid; i < n; i += SAMP_THREADS) {
-        const uint32_t k = samp_key(a.z[i]);
-        const bool in = shift == 28 || (k >> (shift + 4)) == prefix;
-        if (in) {
-          const int nib = (k >> shift) & 15;
-          const double w = a.w[i];
-#pragma unroll
-          for (int b = 0; b < 16; ++b) { acc[b] += nib == b ? w : 0.0; cn[b] += nib == b ? 1 : 0; }
-        }
-      }
-#pragma unroll
-      for (int b = 0; b < 16; ++b) {
-        const double v = xsum(acc[b]); const int c = xsumi(cn[b]);
-        if (lane == 0) { s_bd[wave][b] = v; s_bc[wave][b] = c; }
-      }
-      __syncthreads();
-      if (tid < 16) {
-        double v = 0.0; int c = 0;
-        for (int w = 0; w < NW; ++w) { v += s_bd[w][tid]; c += s_bc[w][tid]; }
-        s_tot[tid] = v; s_cnt[tid] = c;
-      }
-      __syncthreads();
-      if (tid == 0) {
-        double g = s_above; int c = s_nabove, pick = -1;
-        for (int b = 15; b >= 0; --b) {
-          if (s_cnt[b] == 0) continue;
-          const double g2 = g + s_tot[b]; const int c2 = c + s_cnt[b];
-          const bool ok = kind == 0 ? g2 >= T : (kind == 1 ? g2 > T : c2 >= K);
-          // the lowest occupied digit is taken when rounding leaves the bound just unmet everywhere
-          bool last = true;
-          for (int q = b - 1; q >= 0; --q) last = last && s_cnt[q] == 0;
-          if (ok || last) { pick = b; break; }
-          g = g2; c = c2;
-        }
-        if (pick < 0) pick = 0;      // (cannot happen: the digit picked in the pass before was occupied)
-        s_above = g; s_nabove = c; s_prefix = (prefix << 4) | (uint32_t)pick; s_ties = s_cnt[pick];
-      }
+    for (int e = 0; e < VPT; ++e) { const uint32_t k = key[e * KS]; wr[e] = k ? exp((double)samp_unkey(k) - zmax) : 0.0; }
+  } else {
+    for (int i = tid; i < a.npad; i += SAMP_THREADS) {
+      const bool in = i < n;
+      const float z = in ? a.z[i] : 0.f;
+      a.keys[i] = in ? samp_key(z) : 0u;
+      a.w[i] = in ? exp((double)z - zmax) : 0.0;
     }
     __syncthreads();
+  }
+
+  // ---- G(kth): mass and number of the tokens whose key is at least kth (kth >= 1); every thread gets both
+  int par = 0;
+  auto G = [&](uint32_t kth, double& mass, int& count) {
+    double m = 0.0; int c = 0;
+    if (REG) {
+#pragma unroll
+      for (int e = 0; e < VPT; ++e) {
+        const bool ge = key[e * KS] >= kth;
+        m += ge ? wr[e] : 0.0;
+        c += __popcll(__ballot(ge));
+      }
+    } else {
+      for (int i0 = tid; i0 < a.npad; i0 += SAMP_THREADS * SAMP_MEMU) {
+        uint32_t k[SAMP_MEMU]; double w[SAMP_MEMU];
+#pragma unroll
+        for (int q = 0; q < SAMP_MEMU; ++q) { k[q] = a.keys[i0 + q * SAMP_THREADS]; w[q] = a.w[i0 + q * SAMP_THREADS]; }
+#pragma unroll
+        for (int q = 0; q < SAMP_MEMU; ++q) {
+          const bool ge = k[q] >= kth;
+          m += ge ? w[q] : 0.0;
+          c += __popcll(__ballot(ge));
+        }
+      }
+    }
+    m = wave_sum_f64(m);
+    if (lane == 0) { s_m[par][wave] = m; s_c[par][wave] = c; }
+    __syncthreads();
+    mass = 0.0; count = 0;
+    for (int w = 0; w < NW; ++w) { mass += s_m[par][w]; count += s_c[par][w]; }
+    par ^= 1;        // the next evaluation writes the other half: no second barrier needed
+  };
+  // ---- the largest key kappa with G(kappa) >= T (kind 0), G(kappa) > T (kind 1) or count(kappa) >= K (kind 2);
+  // the bound holds at the smallest key present, so kappa >= 1.  Also the mass and count strictly above kappa
+  // and the number of tokens at kappa.
+  auto search = [&](int kind, double T, int K, uint32_t& kappa, double& above, int& nabove, int& ties) {
+    uint32_t pre = 0u;
+    int c_at = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t t = pre | (1u << bit);
+      double g; int c;
+      G(t, g, c);
+      const bool ok = kind == 0 ? g >= T : (kind == 1 ? g > T : c >= K);
+      if (ok) { pre = t; c_at = c; }
+    }
+    kappa = pre;
+    above = 0.0; nabove = 0;
+    if (kappa != 0xffffffffu) G(kappa + 1u, above, nabove);
+    ties = c_at - nabove;
   };
 
-  // ---- kept mass W
+  double S; int n_all;
+  G(1u, S, n_all);
   const int pos_new = a.ds->pos + 1;
   const uint32_t word = philox4x32_10_word0((uint32_t)pos_new, 0u, 0u, 0u, (uint32_t)(a.seed & 0xffffffffu), (uint32_t)(a.seed >> 32));
   const double u = (double)(word >> 8) * (1.0 / 16777216.0);
+  uint32_t kappa; double above; int nabove, ties;
+  // ---- kept mass W (every thread computes the same numbers)
+  double W = S;
   if (a.mode == 1) {
-    int ks = a.ks < 1 ? 1 : a.ks;
-    if (ks >= n) { if (tid == 0) s_W = S; }
-    else {
-      search(2, 0.0, ks);
-      if (tid == 0) {
-        const double wk = exp((double)samp_unkey(s_prefix) - zmax);
-        double W = s_above;
-        for (int r = s_nabove; r < ks; ++r) W += wk;
-        s_W = W;
-      }
+    const int ks = a.ks < 1 ? 1 : a.ks;
+    if (ks < n) {
+      search(2, 0.0, ks, kappa, above, nabove, ties);
+      const double wk = exp((double)samp_unkey(kappa) - zmax);
+      W = above;
+      for (int r = nabove; r < ks; ++r) W += wk;
     }
   } else {
     const double T = a.p * S;
-    search(0, T, 0);
-    if (tid == 0) {
-      const double wk = exp((double)samp_unkey(s_prefix) - zmax);
-      double W = s_above; int r = 0;
-      do { W += wk; ++r; } while (W < T && r < s_ties);
-      s_W = W;
-    }
-  }
-  __syncthreads();
-  // ---- the first token of the ranking whose cumulative mass exceeds u W
-  const double t = u * s_W;
-  search(1, t, 0);
-  const uint32_t kappa = s_prefix;
-  if (tid == 0) {
+    search(0, T, 0, kappa, above, nabove, ties);
     const double wk = exp((double)samp_unkey(kappa) - zmax);
-    double c = s_above; int r = 0;
-    do { c += wk; ++r; } while (!(c > t) && r < s_ties);
-    s_r = r;                       // the r-th smallest id among the tokens at kappa
-    s_min = 0x7fffffff;
+    W = above;
+    int r = 0;
+    do { W += wk; ++r; } while (W < T && r < ties);
   }
+  // ---- the first token of the ranking whose cumulative mass exceeds u W: the r-th smallest id among those at kappa
+  const double t = u * W;
+  search(1, t, 0, kappa, above, nabove, ties);
+  int r = 0;
+  {
+    const double wk = exp((double)samp_unkey(kappa) - zmax);
+    double c = above;
+    do { c += wk; ++r; } while (!(c > t) && r < ties);
+  }
+  if (tid == 0) { s_min = 0x7fffffff; s_prefix = 0u; s_need = r; }
   __syncthreads();
-  const int r = s_r;
   if (r == 1) {
-    for (int i = tid; i < n; i += SAMP_THREADS)
-      if (samp_key(a.z[i]) == kappa) atomicMin(&s_min, i);
+    if (REG) {
+#pragma unroll
+      for (int e = 0; e < VPT; ++e) if (key[e * KS] == kappa) atomicMin(&s_min, tid + e * SAMP_THREADS);
+    } else {
+      for (int i = tid; i < n; i += SAMP_THREADS) if (samp_key(a.z[i]) == kappa) atomicMin(&s_min, i);
+    }
     __syncthreads();
     if (tid == 0) a.ds->sampled = s_min;
     return;
   }
-  // several tokens share the logit: the r-th smallest id among them, again digit by digit (counts, ascending)
-  if (tid == 0) { s_prefix = 0u; s_nabove = r; }
+  // several tokens share the logit and the draw falls past the first of them: the id is fixed four bits at a
+  // time from the top (counts of the tied ids per digit, ascending)
   for (int shift = 28; shift >= 0; shift -= 4) {
     __syncthreads();
     const uint32_t prefix = s_prefix;
@@ -1062,14 +1097,18 @@ __global__ __launch_bounds__(SAMP_THREADS) void sample_kernel(SampleArgs a) {
       }
     }
 #pragma unroll
-    for (int b = 0; b < 16; ++b) { const int c = xsumi(cn[b]); if (lane == 0) s_bc[wave][b] = c; }
+    for (int b = 0; b < 16; ++b) {
+      int c = cn[b];
+      for (int o = 32; o >= 1; o >>= 1) c += __shfl_xor(c, o);
+      if (lane == 0) s_bc[wave][b] = c;
+    }
     __syncthreads();
     if (tid < 16) { int c = 0; for (int w = 0; w < NW; ++w) c += s_bc[w][tid]; s_cnt[tid] = c; }
     __syncthreads();
     if (tid == 0) {
-      int need = s_nabove, pick = 15;
+      int need = s_need, pick = 15;
       for (int b = 0; b < 16; ++b) { if (s_cnt[b] >= need) { pick = b; break; } need -= s_cnt[b]; }
-      s_nabove = need; s_prefix = (prefix << 4) | (uint32_t)pick;
+      s_need = need; s_prefix = (prefix << 4) | (uint32_t)pick;
     }
   }
   __syncthreads();

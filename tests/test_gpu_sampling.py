@@ -127,3 +127,34 @@ def test_equal_logits_and_limits(family):
             P.ppd_set_sampling(*bad, 0)
         assert ei.value.code == -1
     P.close()
+
+
+@pytest.mark.parametrize("mode,ks,p", MODES[:3])
+def test_vocabulary_beyond_the_on_chip_path(mode, ks, p):
+    """More than 32768 logits do not fit the sampling kernel's registers and LDS: it then re-reads keys and
+    weights from memory in every pass.  Same checks as above on a model with 33001 tokens."""
+    cfg = small_cfg("opt", vocab=33001, n_gen=12)
+    m = pi.make_model(cfg)
+    dev = binding.upload_model(m)
+    prompt = pi.make_prompt(cfg)
+    P = binding.PPD(cfg, dev, k=3)
+    P.ppd_set_sampling(mode, ks, p, SEED)
+    ptoks, pz, _ = gpu_generate(P, prompt, cfg.n_gen, "plain")
+    toks, z, _ = gpu_generate(P, prompt, cfg.n_gen, "ppd")
+    np.testing.assert_array_equal(toks, ptoks)
+    np.testing.assert_array_equal(z.view(np.uint32), pz.view(np.uint32))
+    for t in range(cfg.n_gen):
+        u = oracle.uniform(SEED, len(prompt) + t)
+        assert int(toks[t]) == oracle.sample(z[t].astype(np.float64), mode, ks, p, u), (t, u)
+    # equal logits through this path too: token floor(u n)
+    m.g["lm_head"] = np.zeros_like(m.g["lm_head"])
+    if m.g.get("lnf_b") is not None:
+        m.g["lnf_b"] = np.zeros_like(m.g["lnf_b"])
+    P2 = binding.PPD(cfg, binding.upload_model(m), k=3)
+    P2.ppd_set_sampling(oracle.TOP_P, 0, 1.0, SEED)
+    P2.ppd_prefill(prompt)
+    for t in range(4):
+        tok, _ = P2.ppd_step()
+        assert tok == int(oracle.uniform(SEED, len(prompt) + t) * cfg.vocab)
+    P.close()
+    P2.close()
