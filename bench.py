@@ -108,6 +108,9 @@ def main():
         round_ms.append((time.perf_counter() - t) * 1e3)
         round_hit.append(bool(info.matched))
 
+    t = time.perf_counter()
+    P.ppd_prefill(prompt)                  # (synchronous) the prompt in chunks of 8 positions through the decode kernels
+    prefill_s = time.perf_counter() - t
     wall_ppd, _ = timed(P, ppd_round, W, K)
     round_ms, round_hit = np.array(round_ms[W:]), np.array(round_hit[W:])
     # a round's length is set by how it starts: after a hit it resumes mid-stack (no solo phase when dbar = d/2)
@@ -217,6 +220,8 @@ def main():
                                  "measured_total": (st["main_layer_rows"] + st["branch_layer_rows"]) / ell,
                                  "theorem_latency": tradeoff.expected_latency(d, e, ell, p_hat) / ell,
                                  "theorem_compute": tradeoff.expected_compute(d, e, ell, k, p_hat) / ell},
+        "prefill": {"positions": n_prompt - 1, "ms": round(prefill_s * 1e3, 2),
+                    "positions_per_s": round((n_prompt - 1) / prefill_s, 1)},
         "roofline": roof, "pipelined_step": pipe, "kernels": kernels, "cpu_baseline": cpu,
         "setup_s": {"generate_weights": round(t_gen, 1)},
     }

@@ -136,7 +136,13 @@ int ppd_reset(ppd_ctx *ctx);
  * one start token x_0; reading taken for prompts: positions 0..n_prompt-2 are
  * run through all d layers to fill the KV cache, the last prompt token
  * becomes x_0 with match = False.  Implies ppd_reset.  PPD_ECTX if
- * n_prompt > max_ctx; PPD_EINVAL for ids outside [0, vocab). */
+ * n_prompt > max_ctx; PPD_EINVAL for ids outside [0, vocab).
+ * The prompt goes through the decode kernels in chunks of up to eight
+ * consecutive positions (as many rows as a layer's norm-fused GEMMs stage at
+ * once): one pass over the weights per chunk, rows of a chunk attending
+ * causally to each other.  Every row's arithmetic is that of a one-token
+ * pass, so the cache equals a token-by-token prefill bit for bit
+ * (PPD_PREFILL_CHUNK=1 in the environment at ppd_create runs that). */
 int ppd_prefill(ppd_ctx *ctx, const int32_t *prompt, int n_prompt);
 
 /* One round of Algorithm 2: main token to the exit layer (from layer 1, or

@@ -64,6 +64,7 @@ struct ppd_ctx {
   int spec;
   int last_kind;
   // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
+  int prefill_chunk;
   int samp_mode, samp_k; double samp_p; uint64_t samp_seed;
   double* samp_w; uint32_t* samp_keys; int samp_npad;   // scratch of the sampling kernel
   int head_grid;
@@ -189,6 +190,10 @@ hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
   return hipErrorInvalidValue;   // bf16 weights never come here: they take the MFMA kernel
 }
 
+// rows of a prompt chunk (ppd_prefill feeds the prompt through the decode kernels this many positions at a time:
+// one pass over the weights per chunk instead of per token)
+constexpr int PREFILL_CHUNK = 8;
+
 // ---- bf16 models: MFMA GEMM on repacked weights
 constexpr size_t MG_LDS_MAX = 160 * 1024;
 
@@ -245,7 +250,7 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
   };
   // rows whose staged form fits LDS
   int mcap = 0;
-  const int tcap = a.topk > 0 ? t1 : t1 * 2;
+  const int tcap = (a.topk > 0 || (ngroups == 1 && !c->in_dual)) ? t1 : t1 * 2;   // tiles per workgroup of this launch shape
   while (mcap < 16 && lds_for(mcap + 1, tcap) <= MG_LDS_MAX) ++mcap;
   if (a.topk > 0 && mmax > mcap) return hipErrorInvalidValue;   // head launches are never cut into row slices
   if (mmax <= mcap) return go(a, ngroups, mmax);
@@ -270,8 +275,10 @@ hipError_t launch_attn(ppd_ctx* c, const AttnArgs& a, int ngroups, int pmax) {
   dim3 grid(pmax / ATT_CHUNK + 1, a.H, ngroups);
   int mmax = a.g[0].M;
   if (ngroups == 2 && a.g[1].M > mmax) mmax = a.g[1].M;
-  if (c->d.head_dim == 64) return launch_attn_t<64>(c->cur, a, mmax, grid);
-  return launch_attn_t<128>(c->cur, a, mmax, grid);
+  const bool causal = a.g[0].causal != 0;
+  if (causal && ngroups != 1) return hipErrorInvalidValue;
+  if (c->d.head_dim == 64) return launch_attn_t<64>(c->cur, a, mmax, grid, causal);
+  return launch_attn_t<128>(c->cur, a, mmax, grid, causal);
 }
 
 // the same launch described for the MFMA kernel: P[g] = group g's repacked weights
@@ -298,6 +305,7 @@ struct RowGroup {
   int row0;      // 0: main row; 1: first candidate row
   int pos_off;   // the rows' token sits at position (device state pos) + pos_off
   bool tail;     // own K/V go to the candidate tails (slot = row index) instead of the cache
+  bool chunk = false;   // prompt chunk: row m sits m positions further on and sees the rows before it
 };
 
 // One transformer layer for one or two row groups (a pipelined step when two).
@@ -343,6 +351,16 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages 
       G.own_cache = rg[g].tail ? 0 : 1;
       G.part = c->part + (size_t)rg[g].row0 * part_row;
       G.pos_off = rg[g].pos_off; G.M = rg[g].M;
+      G.causal = rg[g].chunk ? 1 : 0; mg.causal[g] = G.causal;
+      if (rg[g].chunk) {
+        // keys and values of all rows of the chunk go into the cache first
+        if (ngroups != 1 || rg[g].tail || rg[g].pos_off != 0) return PPD_EINVAL;
+        ChunkKvArgs kv; memset(&kv, 0, sizeof kv);
+        kv.qkv = G.qkv; kv.Kc = G.Kc; kv.Vc = G.Vc; kv.rope = d.pos == 1 ? c->rope : nullptr; kv.ds = c->ds;
+        kv.HD = d.head_dim; kv.d_model = dm; kv.max_ctx = d.max_ctx;
+        hipLaunchKernelGGL(chunk_kv_kernel, dim3(G.M, d.n_heads), dim3(d.head_dim), 0, c->cur, kv);
+        HIPCHK(c, hipGetLastError());
+      }
       mg.part[g] = G.part; mg.out[g] = c->att + (size_t)rg[g].row0 * dm; mg.pos_off[g] = G.pos_off; mg.M[g] = G.M;
     }
     a.ds = c->ds; mg.ds = c->ds;
@@ -417,7 +435,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages 
 EmbedArgs embed_args(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos_off) {
   EmbedArgs a;
   a.tok_emb = c->tok_emb; a.pos_emb = c->d.pos == 0 ? c->pos_emb : nullptr; a.ids = ids_dev; a.ds = c->ds;
-  a.h = c->h + (size_t)row0 * c->d.d_model; a.rows = rows; a.d_model = c->d.d_model; a.pos_off = pos_off;
+  a.h = c->h + (size_t)row0 * c->d.d_model; a.rows = rows; a.d_model = c->d.d_model; a.pos_off = pos_off; a.pos_step = 0;
   return a;
 }
 
@@ -686,6 +704,8 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   c->use_graphs = env_int("PPD_GRAPHS", 1) != 2;      // PPD_GRAPHS=2 switches graph replay off
   c->dual = env_int("PPD_DUAL", 1) != 2;               // PPD_DUAL=2: two-group launches instead of two chains
   c->skew = env_int("PPD_SKEW", 0) == 1;
+  c->prefill_chunk = env_int("PPD_PREFILL_CHUNK", PREFILL_CHUNK);
+  if (c->prefill_chunk > PREFILL_CHUNK) c->prefill_chunk = PREFILL_CHUNK;
   c->gmax1 = env_int("PPD_GMAX1", 512);
   c->gmaxd = env_int("PPD_GMAXD", 256);
   c->gmax2 = env_int("PPD_GMAX2", 256);
@@ -699,17 +719,18 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     c->head_grid = g;
   }
   const size_t dm = d.d_model, R = 1 + k;
+  const size_t RB = R > PREFILL_CHUNK ? R : PREFILL_CHUNK;   // activation rows: a round's 1 + k, or a prompt chunk
   hipError_t e = hipSuccess;
   auto alloc = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes); };
   alloc((void**)&c->Kc, (size_t)d.n_layers * cache_layer_bytes(c));
   alloc((void**)&c->Vc, (size_t)d.n_layers * cache_layer_bytes(c));
   alloc((void**)&c->tailK, (size_t)c->nb * k * dm * c->kvbytes);
   alloc((void**)&c->tailV, (size_t)c->nb * k * dm * c->kvbytes);
-  alloc((void**)&c->h, R * dm * sizeof(float));
-  alloc((void**)&c->qkv, R * 3 * dm * sizeof(float));
-  alloc((void**)&c->att, R * dm * sizeof(float));
-  alloc((void**)&c->ffn, R * (size_t)d.d_ff * sizeof(float));
-  alloc((void**)&c->part, R * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
+  alloc((void**)&c->h, RB * dm * sizeof(float));
+  alloc((void**)&c->qkv, RB * 3 * dm * sizeof(float));
+  alloc((void**)&c->att, RB * dm * sizeof(float));
+  alloc((void**)&c->ffn, RB * (size_t)d.d_ff * sizeof(float));
+  alloc((void**)&c->part, RB * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
   alloc((void**)&c->logits, R * d.vocab * sizeof(float));
   alloc((void**)&c->early_spec, (size_t)2 * d.vocab * sizeof(float));
   c->samp_npad = (d.vocab + SAMP_THREADS * SAMP_MEMU - 1) / (SAMP_THREADS * SAMP_MEMU) * (SAMP_THREADS * SAMP_MEMU);
@@ -791,6 +812,22 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     while ((NTh + c->head_grid - 1) / c->head_grid > HEAD_MAX_ROWS / 16) ++c->head_grid;
     if ((size_t)c->head_grid > pk_slots) e = hipErrorInvalidValue;
     if (env_int("PPD_DUAL", 2) != 1) c->dual = 0;   // one launch per step for both chains unless asked otherwise
+    // prompt chunks: as many rows as the two norm-fused GEMMs of a layer stage in LDS at once, so that a
+    // chunk costs one pass over the weights (more rows would be cut into slices, each streaming them again)
+    {
+      const int KT = ((int)dm + 31) / 32, xrow = mg_xrow(KT);
+      const int nt_qkv = (3 * (int)dm + 15) / 16, nt_fin = d.act == 2 ? (d.d_ff + 7) / 8 : (d.d_ff + 15) / 16;
+      const int nts[2] = {nt_qkv, nt_fin};
+      int cap = PREFILL_CHUNK;
+      for (int q = 0; q < 2; ++q) {
+        const int t1 = (nts[q] + 255) / 256;
+        int ob, op, ox, m = 0;
+        while (m < 16 && (size_t)mg_lds_layout((int)dm, m + 1, d.norm, t1, xrow, ob, op, ox) <= MG_LDS_MAX) ++m;
+        if (m < cap) cap = m;
+      }
+      if (cap < 1) cap = 1;
+      if (c->prefill_chunk > cap) c->prefill_chunk = cap;
+    }
     // speculative early prediction when the candidates end a round at the exit layer, the early head is the LM
     // head, and the 1 + k rows of the widened final head fit one launch (PPD_SPEC=2 switches it off)
     {
@@ -834,12 +871,24 @@ int ppd_prefill(ppd_ctx* c, const int32_t* prompt, int n_prompt) {
   HIPCHK(c, hipMemcpyAsync(c->prompt_dev, prompt, (size_t)n_prompt * sizeof(int32_t), hipMemcpyHostToDevice, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));   // prompt is pageable host memory of the caller
   int prof = c->prof; c->prof = 0;
-  for (int i = 0; i + 1 < n_prompt && !rc; ++i) {
+  // positions 0 .. n_prompt-2 in chunks of consecutive positions: every row's arithmetic is that of a
+  // token-by-token pass (PPD_PREFILL_CHUNK=1 runs exactly that), the weights are streamed once per chunk
+  const int chunk = c->prefill_chunk;
+  for (int i = 0; i + 1 < n_prompt && !rc; i += chunk) {
+    const int m = n_prompt - 1 - i < chunk ? n_prompt - 1 - i : chunk;
     rc = set_state(c, i, -1);
-    if (!rc) rc = run_embed(c, c->prompt_dev + i, 1, 0, 0);
+    if (!rc) {
+      EmbedArgs ea = embed_args(c, c->prompt_dev + i, m, 0, 0);
+      ea.pos_step = 1;
+      dim3 grid((c->d.d_model + 255) / 256, m);
+      if (c->wbytes == 4) hipLaunchKernelGGL(embed_kernel<float>, grid, dim3(256), 0, c->cur, ea);
+      else hipLaunchKernelGGL(embed_kernel<bf16_t>, grid, dim3(256), 0, c->cur, ea);
+      if (hipGetLastError() != hipSuccess) rc = PPD_EHIP;
+    }
     for (int l = 0; l < c->d.n_layers && !rc; ++l) {
-      RowGroup g{l, 1, 0, 0, false};
-      rc = run_layer(c, 1, &g, i);
+      RowGroup g{l, m, 0, 0, false};
+      g.chunk = m > 1;
+      rc = run_layer(c, 1, &g, i + m - 1);
     }
   }
   c->prof = prof;

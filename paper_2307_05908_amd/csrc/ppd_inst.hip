@@ -39,20 +39,21 @@ template hipError_t launch_gemm_t<float, false, 2>(hipStream_t, const GemmArgs&,
 template hipError_t launch_gemm_t<float, true, 2>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
 #endif
 #else
-// mmax: the largest row count of the launch's groups (sizes LDS)
+// mmax: the largest row count of the launch's groups (sizes LDS); causal: the prompt-chunk instance
 template <int HD>
-hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int mmax, dim3 grid) {
+hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int mmax, dim3 grid, bool causal) {
   if (mmax < 1 || mmax > 16) return hipErrorInvalidValue;
   const size_t lds = sizeof(float) * (size_t)attn_lds_floats<HD>(mmax);
   if (lds > 64 * 1024) return hipErrorInvalidValue;     // the default dynamic LDS limit
-  attn_kernel<HD><<<grid, dim3(ATT_THREADS), lds, stream>>>(a);
+  if (causal) attn_kernel<HD, true><<<grid, dim3(ATT_THREADS), lds, stream>>>(a);
+  else attn_kernel<HD, false><<<grid, dim3(ATT_THREADS), lds, stream>>>(a);
   return hipGetLastError();
 }
 
 #if PPD_INST == 4
-template hipError_t launch_attn_t<128>(hipStream_t, const AttnArgs&, int, dim3);
+template hipError_t launch_attn_t<128>(hipStream_t, const AttnArgs&, int, dim3, bool);
 #elif PPD_INST == 5
-template hipError_t launch_attn_t<64>(hipStream_t, const AttnArgs&, int, dim3);
+template hipError_t launch_attn_t<64>(hipStream_t, const AttnArgs&, int, dim3, bool);
 #endif
 #endif
 

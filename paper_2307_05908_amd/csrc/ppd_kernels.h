@@ -154,12 +154,13 @@ struct EmbedArgs {
   const int32_t* ids;   // DEVICE: token id of row r is ids[r]
   const DevState* ds;
   float* h;             // [rows][d_model]
-  int rows, d_model, pos_off;   // the rows sit at position ds->pos + pos_off
+  int rows, d_model, pos_off;   // the rows sit at position ds->pos + pos_off (+ r * pos_step for row r)
+  int pos_step;
 };
 template <typename WT>
 __device__ __forceinline__ void embed_rows(const EmbedArgs& a, int r, int i0, int stride) {
   int tok = a.ids[r];
-  int pos = a.ds->pos + a.pos_off;
+  int pos = a.ds->pos + a.pos_off + r * a.pos_step;
   for (int i = i0; i < a.d_model; i += stride) {
     float v = WTr<WT>::load1(a.tok_emb, (size_t)tok * a.d_model + i);
     if (a.pos_emb) v += WTr<WT>::load1(a.pos_emb, (size_t)pos * a.d_model + i);
@@ -613,6 +614,8 @@ struct AttnGroup {
   int pos_off;          // the rows sit at position p = ds->pos + pos_off and attend to cached positions [0, p)
   int own_cache;        // the row's own key/value go to cache position p (one row only)
   int M;                // rows, 1..16
+  int causal;           // prompt chunk: row m sits at position p + m and attends to [0, p + m); the keys and
+                        // values of all rows are in the cache already (chunk_kv_kernel), nothing is stored here
 };
 struct AttnArgs {
   AttnGroup g[2];
@@ -627,7 +630,7 @@ template <int HD> __host__ __device__ constexpr int attn_lds_floats(int M) {
   return M * (3 * HD + 3 * HD + ATT_CHUNK + 4 + ATT_WAVES * HD);
 }
 
-template <int HD>
+template <int HD, bool CAUSAL = false>
 __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
   extern __shared__ float4 lds4[];
   float* lds = (float*)lds4;
@@ -638,8 +641,11 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
   const int h = blockIdx.y, c = blockIdx.x;
   const int p = a.ds->pos + G.pos_off, M = G.M;
   const int j0 = c * ATT_CHUNK;
-  if (j0 > p) return;
-  const bool owns_p = (p < j0 + ATT_CHUNK);
+  if (j0 > p + (CAUSAL ? M - 1 : 0)) return;
+  // position of row m; whether this chunk holds it; whether the chunk lies before or at it at all
+  auto pos_of = [&](int m) { return CAUSAL ? p + m : p; };
+  auto owns = [&](int m) { const int pm = pos_of(m); return pm >= j0 && pm < j0 + ATT_CHUNK; };
+  auto live = [&](int m) { return !CAUSAL || j0 <= pos_of(m); };
   float* raw = lds;                   // [M][3][HD]
   float* qs = raw + M * 3 * HD;       // [M][HD]
   float* ko = qs + M * HD;            // [M][HD]
@@ -681,6 +687,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
     const float* r = raw + m * 3 * HD;
     float q = r[i], k = r[HD + i];
     const float v = r[2 * HD + i];
+    if (CAUSAL && a.rope) cz = a.rope[(size_t)pos_of(m) * half + (i < half ? i : i - half)];
     if (a.rope) {
       const int ip = i < half ? i + half : i - half;
       const float qo = r[ip], kk = r[HD + ip];
@@ -710,28 +717,30 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
     if (bn < M) {
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
-        const int jl = 16 * wave + 4 * bc + jj, j = j0 + jl;
-        if (j != p) sc[bn * ATT_CHUNK + jl] = j < p ? sacc[jj] : -INFINITY;
+        const int jl = 16 * wave + 4 * bc + jj, j = j0 + jl, pm = pos_of(bn);
+        if (j != pm) sc[bn * ATT_CHUNK + jl] = j < pm ? sacc[jj] : -INFINITY;
       }
     }
   }
-  if (owns_p) {
+  {
     for (int m = wave; m < M; m += ATT_WAVES) {
+      if (!owns(m)) continue;
       float s = 0.f;
 #pragma unroll
       for (int e = 0; e < HD / WAVE; ++e) s = fmaf(qs[m * HD + lane + e * WAVE], ko[m * HD + lane + e * WAVE], s);
       s = wave_sum(s);
-      if (lane == 0) sc[m * ATT_CHUNK + (p - j0)] = s;
+      if (lane == 0) sc[m * ATT_CHUNK + (pos_of(m) - j0)] = s;
     }
   }
   __syncthreads();
   // chunk-local softmax numerators: one wave per row, one position per lane
   for (int m = wave; m < M; m += ATT_WAVES) {
+    if (!live(m)) continue;      // (the chunk lies past this row: its scores are not used and nothing is written for it)
     const float v = sc[m * ATT_CHUNK + lane];
     const float mx = wave_max(v);
     const float e = expf(v - mx);
     const float sum = wave_sum(e);
-    const bool own = owns_p && lane == p - j0;
+    const bool own = owns(m) && lane == pos_of(m) - j0;
     sc[m * ATT_CHUNK + lane] = own ? 0.f : e;       // the own position is added outside the MFMAs
     if (own) st[m * 4 + 2] = e;
     if (lane == 0) { st[m * 4] = mx; st[m * 4 + 1] = sum; }
@@ -753,6 +762,8 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
   // the four blocks in wave order, then the rows' own position
   for (int idx = tid; idx < M * HD; idx += ATT_THREADS) {
     const int m = idx / HD, i = idx - m * HD;
+    if (!live(m)) continue;
+    const bool owns_p = owns(m);
     float o = ored[(0 * M + m) * HD + i];
 #pragma unroll
     for (int w = 1; w < ATT_WAVES; ++w) o += ored[(w * M + m) * HD + i];
@@ -761,7 +772,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
     dst[i] = o;
     if (i == 0) { dst[HD] = st[m * 4]; dst[HD + 1] = st[m * 4 + 1]; }
     // the row's own key and value (stored last: no store waits in the request queue behind the block loads)
-    if (owns_p) {
+    if (owns_p && !CAUSAL) {
       if (G.own_cache) {
         const size_t base = (size_t)h * kv_blocks(a.max_ctx) * (KV_BLOCK * HD);
         G.Kc[base + k_index(p, i, HD)] = ko[m * HD + i];
@@ -775,10 +786,40 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
   }
 }
 
+// Prompt chunk: rows m = 0..M-1 sit at consecutive positions p + m.  Their keys (rotated exactly as the
+// attention kernel rotates a row's own key) and values go into the cache before the chunk's attention runs,
+// so that every row finds the rows before it there.  One workgroup per (row, head), one thread per component.
+struct ChunkKvArgs {
+  const float* qkv;     // [M][3*d_model]
+  float* Kc; float* Vc; // this layer's cache
+  const float2* rope;
+  const DevState* ds;
+  int HD, d_model, max_ctx;
+};
+#ifdef PPD_ENGINE_TU
+__global__ void chunk_kv_kernel(ChunkKvArgs a) {
+  const int m = blockIdx.x, h = blockIdx.y, i = threadIdx.x, HD = a.HD, half = HD / 2;
+  const int pos = a.ds->pos + m;
+  const float* r = a.qkv + (size_t)m * 3 * a.d_model + (size_t)h * HD;
+  float k = r[a.d_model + i];
+  const float v = r[2 * a.d_model + i];
+  if (a.rope) {
+    const float2 cz = a.rope[(size_t)pos * half + (i < half ? i : i - half)];
+    const float kk = r[a.d_model + (i < half ? i + half : i - half)];
+    if (i < half) k = fmaf(k, cz.x, -(kk * cz.y));
+    else          k = fmaf(k, cz.x, kk * cz.y);
+  }
+  const size_t base = (size_t)h * kv_blocks(a.max_ctx) * (KV_BLOCK * HD);
+  a.Kc[base + k_index(pos, i, HD)] = k;
+  a.Vc[base + v_index(pos, i, HD)] = v;
+}
+#endif
+
 // merge of the chunk partials, chunks in index order
 struct MergeArgs {
   const float* part[2]; float* out[2];   // out: [M][d_model]
   int pos_off[2]; int M[2];
+  int causal[2];       // row m sits m positions further on (prompt chunk)
   const DevState* ds;
   int H, HD, d_model, nchunk_max;
 };
@@ -791,7 +832,7 @@ __global__ __launch_bounds__(MERGE_THREADS) void attn_merge_kernel(MergeArgs a) 
   __shared__ float sm_o[MERGE_THREADS], sl_m[8], sl_l[8];
   const int g = blockIdx.z, h = blockIdx.y, m = blockIdx.x;
   if (m >= a.M[g]) return;
-  const int nc = (a.ds->pos + a.pos_off[g]) / ATT_CHUNK + 1;
+  const int nc = (a.ds->pos + a.pos_off[g] + (a.causal[g] ? m : 0)) / ATT_CHUNK + 1;
   const int S = MERGE_THREADS / a.HD;          // 4 (head_dim 128) or 8 (64)
   const int i = threadIdx.x % a.HD, sl = threadIdx.x / a.HD;
   const float* base = a.part[g] + (((size_t)m * a.H + h) * a.nchunk_max) * (a.HD + 2);

@@ -9,6 +9,6 @@ template <typename WT, bool PAIRED, int WR>
 hipError_t launch_gemm_t(hipStream_t stream, const GemmArgs& a, int MA, int MB, dim3 grid, size_t lds);
 
 template <int HD>
-hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int mmax, dim3 grid);
+hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int mmax, dim3 grid, bool causal);
 
 }  // namespace ppd

@@ -268,3 +268,32 @@ def test_speculative_early_prediction_changes_nothing_but_the_traffic(family, k,
         head_bytes = cfg.vocab * cfg.d_model * cfg.wbytes
         assert st0["weight_bytes"] - st1["weight_bytes"] == follow * head_bytes
         assert follow > 0
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", list(SMALL))
+def test_prompt_in_chunks_is_token_by_token_bit_exact(name, monkeypatch):
+    """ppd_prefill feeds the prompt eight positions at a time (one pass over the weights per chunk, rows of a
+    chunk attend causally to each other); every row's arithmetic is that of a one-token pass, so the cache and
+    everything decoded from it equal the token-by-token prefill (PPD_PREFILL_CHUNK=1) bit for bit.  Prompt
+    lengths leave ragged last chunks and cross the 64-position attention chunks."""
+    cfg = SMALL[name]
+    dev = binding.upload_model(pi.make_model(cfg))
+
+    def run(n_prompt):
+        prompt = pi.make_prompt(cfg, n_prompt)
+        P = binding.PPD(cfg, dev, k=3)
+        toks, z, _ = gpu_generate(P, prompt, 6, "ppd")
+        ptoks, pz, _ = gpu_generate(P, prompt, 3, "plain")
+        P.close()
+        return toks, z, ptoks, pz
+
+    lengths = sorted({2, 3, 9, 10, cfg.n_prompt, min(cfg.max_ctx - 8, 70), min(cfg.max_ctx - 8, 130)})
+    got = {n: run(n) for n in lengths}
+    monkeypatch.setenv("PPD_PREFILL_CHUNK", "1")
+    for n in lengths:
+        ref = run(n)
+        for a, b in zip(got[n], ref):
+            np.testing.assert_array_equal(np.asarray(a).view(np.uint32) if np.asarray(a).dtype == np.float32 else a,
+                                          np.asarray(b).view(np.uint32) if np.asarray(b).dtype == np.float32 else b)
+    monkeypatch.delenv("PPD_PREFILL_CHUNK")
