@@ -159,9 +159,9 @@ def main():
         if cfg.wdtype != pi.WD_BF16:
             kname = "gemm_kernel<float, 1, 0, %s, WR> (norm + first FFN matrix + activation), one row" % ("true" if n_in == 2 else "false")
         elif n_in == 2:
-            kname = "gemm_mfma_kernel<true> (norm + FFN-in gate and up matrices + SwiGLU), one row"
+            kname = "gemm_mfma_kernel<true, false> (norm + FFN-in gate and up matrices + SwiGLU), one row"
         else:
-            kname = "gemm_mfma_kernel<false> (norm + first FFN matrix + activation), one row"
+            kname = "gemm_mfma_kernel<false, false> (norm + first FFN matrix + activation), one row"
         roof = {"bound": "hbm", "kernel": kname, "achieved": round(ach, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get(cfg.name) if cfg.name.startswith("llama7b") else None,
