@@ -131,6 +131,53 @@ def test_llama7b_full_config_k135():
     check_against_golden("llama7b", "llama7b", (3, 1, 5))
 
 
+@pytest.mark.parametrize("mode,ks,p", [(oracle.TOP_K, 3, 1.0), (oracle.TOP_P, 0, 0.95)])
+def test_llama7b_sampling_full_config(mode, ks, p):
+    """Appendix B at the benchmark's own size (32000 logits, prompt 512, the launch configuration bench.py
+    times): PPD draws the tokens of plain sampling bit for bit, and every token is the oracle's sampler's
+    choice on the GPU's own logits with that position's uniform (both decide in fp64)."""
+    cfg, m, dev = model_on_gpu("llama7b")
+    prompt = pi.make_prompt(cfg)
+    P = binding.PPD(cfg, dev)
+    P.ppd_set_sampling(mode, ks, p, 77)
+    n = 24
+    toks, z, _ = gpu_generate(P, prompt, n, "ppd")
+    ptoks, pz, _ = gpu_generate(P, prompt, n, "plain")
+    np.testing.assert_array_equal(toks, ptoks)
+    np.testing.assert_array_equal(z.view(np.uint32), pz.view(np.uint32))
+    for t in range(n):
+        u = oracle.uniform(77, len(prompt) + t)
+        assert int(toks[t]) == oracle.sample(z[t].astype(np.float64), mode, ks, p, u), (t, u)
+    P.close()
+
+
+def test_llama7b_speculative_early_prediction_full_config(monkeypatch):
+    """The (1 + k)-row final head of the 7B shape with a high match rate (alpha = 0.02 variant is not needed:
+    the check is bit equality with rounds that run their own early head, whatever the rate)."""
+    cfg, m, dev = model_on_gpu("llama7b")
+    prompt = pi.make_prompt(cfg)
+
+    def run():
+        P = binding.PPD(cfg, dev, k=5)
+        P.ppd_prefill(prompt)
+        out = []
+        for _ in range(32):
+            tok, info = P.ppd_step(want_info=True)
+            out.append((tok, info.matched, info.match_idx, tuple(info.cand[:5]),
+                        P.ppd_get_logits().tobytes(), P.ppd_get_early_logits().tobytes()))
+        st = P.ppd_get_stats()
+        P.close()
+        return out, st
+
+    a, sa = run()
+    monkeypatch.setenv("PPD_SPEC", "2")
+    b, sb = run()
+    monkeypatch.delenv("PPD_SPEC")
+    assert a == b
+    follow = sum(1 for j in range(1, len(a)) if a[j - 1][1])
+    assert sb["weight_bytes"] - sa["weight_bytes"] == follow * cfg.head_weight_bytes()
+
+
 @pytest.mark.parametrize("name", ["llama7b_a1", "llama7b_a0p1", "llama7b_a0p02"])
 def test_llama7b_controlled_match_rate(name):
     if not os.path.exists(os.path.join(GOLD, name + ".npz")):
