@@ -65,6 +65,7 @@ struct ppd_ctx {
   int last_kind;
   // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
   int prefill_chunk;
+  float* xn;      // [rows][d_model] normalised rows of a prompt chunk (norm_rows_kernel)
   int samp_mode, samp_k; double samp_p; uint64_t samp_seed;
   double* samp_w; uint32_t* samp_keys; int samp_npad;   // scratch of the sampling kernel
   int head_grid;
@@ -191,8 +192,12 @@ hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
 }
 
 // rows of a prompt chunk (ppd_prefill feeds the prompt through the decode kernels this many positions at a time:
-// one pass over the weights per chunk instead of per token)
-constexpr int PREFILL_CHUNK = 8;
+// one pass over the weights per chunk instead of per token): up to the 16 columns of an MFMA tile for bf16 models
+// (12 by default: measured fastest on the 7B and 13B shapes, where more rows mean more staging passes per
+// GEMM), the 8 rows of the fp32 GEMM otherwise
+constexpr int PREFILL_CHUNK = 16;
+constexpr int PREFILL_CHUNK_DEFAULT = 12;
+constexpr int PREFILL_CHUNK_FP32 = 8;
 
 // ---- bf16 models: MFMA GEMM on repacked weights
 constexpr size_t MG_LDS_MAX = 160 * 1024;
@@ -242,8 +247,8 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
     if (lds > MG_LDS_MAX || (x.topk > 0 && x.tiles_wg * 16 > HEAD_MAX_ROWS)) return hipErrorInvalidValue;
     dim3 grid(gx, ng);
     if (x.passes > 1) {
-      if (paired) return hipErrorInvalidValue;       // (paired launches carry a fused norm: always one pass)
-      hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), grid, dim3(MG_THREADS), lds, c->cur, x);
+      if (paired) hipLaunchKernelGGL((gemm_mfma_kernel<true, true>), grid, dim3(MG_THREADS), lds, c->cur, x);
+      else hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), grid, dim3(MG_THREADS), lds, c->cur, x);
     } else if (paired) hipLaunchKernelGGL((gemm_mfma_kernel<true, false>), grid, dim3(MG_THREADS), lds, c->cur, x);
     else hipLaunchKernelGGL((gemm_mfma_kernel<false, false>), grid, dim3(MG_THREADS), lds, c->cur, x);
     return hipGetLastError();
@@ -308,6 +313,17 @@ struct RowGroup {
   bool chunk = false;   // prompt chunk: row m sits m positions further on and sees the rows before it
 };
 
+// Prompt chunk: the rows of group 0 are normalised by a kernel of their own (same arithmetic as the fused norm)
+// and the GEMM runs without a fused norm on the result, so that it can stage its rows in passes.
+int norm_chunk(ppd_ctx* c, GemmArgs& a, const void* gain, const void* bias) {
+  NormRowsArgs n; memset(&n, 0, sizeof n);
+  n.X = a.g[0].X; n.Y = c->xn; n.g = gain; n.b = bias; n.K = a.K; n.ld = a.ldx; n.norm = a.norm; n.eps = a.eps;
+  hipLaunchKernelGGL(norm_rows_kernel, dim3(a.g[0].M), dim3(MG_THREADS), 0, c->cur, n);
+  HIPCHK(c, hipGetLastError());
+  a.g[0].X = c->xn; a.g[0].ng = nullptr; a.g[0].nb = nullptr; a.norm = -1;
+  return PPD_OK;
+}
+
 // One transformer layer for one or two row groups (a pipelined step when two).
 // pmax: host-side upper bound of the rows' positions (sizes the attention grid only).
 int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages = 15) {
@@ -328,6 +344,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages 
     }
     a.K = dm; a.N[0] = a.N[1] = a.N[2] = dm; a.ntot = 3 * dm; a.ldx = dm; a.ldy = 3 * dm;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
+    if (rg[0].chunk && c->mfma) { int rc = norm_chunk(c, a, c->L[rg[0].layer].ln1_g, d.norm == 0 ? c->L[rg[0].layer].ln1_b : nullptr); if (rc) return rc; }
     ProfScope ps(c, PPD_KC_GEMM_QKV, ngroups);
     if (c->mfma) {
       void* P[2] = {c->LP[rg[0].layer].qkv, ngroups == 2 ? c->LP[rg[1].layer].qkv : nullptr};
@@ -405,6 +422,7 @@ int run_layer(ppd_ctx* c, int ngroups, const RowGroup* rg, int pmax, int stages 
     }
     a.K = dm; a.N[0] = F; a.N[1] = swiglu ? F : 0; a.ntot = F; a.ldx = dm; a.ldy = F;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = swiglu ? 3 : (d.act == 0 ? 1 : 2);
+    if (rg[0].chunk && c->mfma) { int rc = norm_chunk(c, a, c->L[rg[0].layer].ln2_g, d.norm == 0 ? c->L[rg[0].layer].ln2_b : nullptr); if (rc) return rc; }
     ProfScope ps(c, PPD_KC_GEMM_FFN_IN, ngroups);
     if (c->mfma) {
       void* P[2] = {c->LP[rg[0].layer].fin, ngroups == 2 ? c->LP[rg[1].layer].fin : nullptr};
@@ -634,7 +652,7 @@ void account_round(ppd_ctx* c, int kind, int pos) {
 void free_all(ppd_ctx* c) {
   for (int i = 0; i < 4; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
-                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
+                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->xn, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
@@ -704,8 +722,11 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   c->use_graphs = env_int("PPD_GRAPHS", 1) != 2;      // PPD_GRAPHS=2 switches graph replay off
   c->dual = env_int("PPD_DUAL", 1) != 2;               // PPD_DUAL=2: two-group launches instead of two chains
   c->skew = env_int("PPD_SKEW", 0) == 1;
-  c->prefill_chunk = env_int("PPD_PREFILL_CHUNK", PREFILL_CHUNK);
-  if (c->prefill_chunk > PREFILL_CHUNK) c->prefill_chunk = PREFILL_CHUNK;
+  {
+    const int cap = d.wdtype == 1 ? PREFILL_CHUNK : PREFILL_CHUNK_FP32;
+    c->prefill_chunk = env_int("PPD_PREFILL_CHUNK", d.wdtype == 1 ? PREFILL_CHUNK_DEFAULT : cap);
+    if (c->prefill_chunk > cap) c->prefill_chunk = cap;
+  }
   c->gmax1 = env_int("PPD_GMAX1", 512);
   c->gmaxd = env_int("PPD_GMAXD", 256);
   c->gmax2 = env_int("PPD_GMAX2", 256);
@@ -729,6 +750,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   alloc((void**)&c->h, RB * dm * sizeof(float));
   alloc((void**)&c->qkv, RB * 3 * dm * sizeof(float));
   alloc((void**)&c->att, RB * dm * sizeof(float));
+  alloc((void**)&c->xn, RB * dm * sizeof(float));
   alloc((void**)&c->ffn, RB * (size_t)d.d_ff * sizeof(float));
   alloc((void**)&c->part, RB * d.n_heads * (size_t)c->nchunk_max * (d.head_dim + 2) * sizeof(float));
   alloc((void**)&c->logits, R * d.vocab * sizeof(float));
@@ -801,6 +823,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
     // head launches: the same balanced grid as any other GEMM; a workgroup keeps at most
     // HEAD_MAX_ROWS logits = 16 tiles
     c->mg_occ = env_int("PPD_MGOCC", 1) == 2 ? 2 : 1;
@@ -812,22 +835,6 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     while ((NTh + c->head_grid - 1) / c->head_grid > HEAD_MAX_ROWS / 16) ++c->head_grid;
     if ((size_t)c->head_grid > pk_slots) e = hipErrorInvalidValue;
     if (env_int("PPD_DUAL", 2) != 1) c->dual = 0;   // one launch per step for both chains unless asked otherwise
-    // prompt chunks: as many rows as the two norm-fused GEMMs of a layer stage in LDS at once, so that a
-    // chunk costs one pass over the weights (more rows would be cut into slices, each streaming them again)
-    {
-      const int KT = ((int)dm + 31) / 32, xrow = mg_xrow(KT);
-      const int nt_qkv = (3 * (int)dm + 15) / 16, nt_fin = d.act == 2 ? (d.d_ff + 7) / 8 : (d.d_ff + 15) / 16;
-      const int nts[2] = {nt_qkv, nt_fin};
-      int cap = PREFILL_CHUNK;
-      for (int q = 0; q < 2; ++q) {
-        const int t1 = (nts[q] + 255) / 256;
-        int ob, op, ox, m = 0;
-        while (m < 16 && (size_t)mg_lds_layout((int)dm, m + 1, d.norm, t1, xrow, ob, op, ox) <= MG_LDS_MAX) ++m;
-        if (m < cap) cap = m;
-      }
-      if (cap < 1) cap = 1;
-      if (c->prefill_chunk > cap) c->prefill_chunk = cap;
-    }
     // speculative early prediction when the candidates end a round at the exit layer, the early head is the LM
     // head, and the 1 + k rows of the widened final head fit one launch (PPD_SPEC=2 switches it off)
     {

@@ -1763,4 +1763,67 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
   }
 }
 
+// The norm of gemm_mfma_kernel's prologue on its own: Y = norm(X) row by row, with the same order of additions
+// (thread t sums the 8-element pieces t, t + 512, ...; butterfly inside each wave; the eight wave sums in index
+// order) and the same expression per element, so that a GEMM without a fused norm on Y gives the bits of the
+// fused one on X.  For row groups whose rows do not fit LDS whole (prompt chunks): the GEMM then stages Y in passes.
+#ifdef PPD_ENGINE_TU
+struct NormRowsArgs {
+  const float* X; float* Y;      // [M][ld]
+  const void* g; const void* b;  // bf16 gain, bias (LayerNorm) or null
+  int K, ld, norm;               // norm: 0 LayerNorm, 1 RMSNorm
+  float eps;
+};
+__global__ __launch_bounds__(MG_THREADS) void norm_rows_kernel(NormRowsArgs a) {
+  __shared__ float redA[MG_WAVES], redB[MG_WAVES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, K = a.K;
+  const float* x = a.X + (size_t)blockIdx.x * a.ld;
+  float* y = a.Y + (size_t)blockIdx.x * a.ld;
+  auto combine8 = [&](const float* r) { return ((((((r[0] + r[1]) + r[2]) + r[3]) + r[4]) + r[5]) + r[6]) + r[7]; };
+  float mu = 0.f;
+  if (a.norm == 0) {
+    float sm = 0.f;
+    for (int c = tid; c * 8 < K; c += MG_THREADS) {
+      const float4* px = (const float4*)(x + c * 8);
+      const float4 v = px[0], w = px[1];
+      sm += v.x; sm += v.y; sm += v.z; sm += v.w; sm += w.x; sm += w.y; sm += w.z; sm += w.w;
+    }
+    sm = wave_sum(sm);
+    if (lane == 0) redA[wave] = sm;
+    __syncthreads();
+    mu = combine8(redA) / (float)K;
+  }
+  float s2 = 0.f;
+  for (int c = tid; c * 8 < K; c += MG_THREADS) {
+    const float4* px = (const float4*)(x + c * 8);
+    const float4 v = px[0], w = px[1];
+    const float d[8] = {v.x - mu, v.y - mu, v.z - mu, v.w - mu, w.x - mu, w.y - mu, w.z - mu, w.w - mu};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s2 = fmaf(d[e], d[e], s2);
+  }
+  s2 = wave_sum(s2);
+  if (lane == 0) redB[wave] = s2;
+  __syncthreads();
+  const float rs = 1.0f / sqrtf(combine8(redB) / (float)K + a.eps);
+  for (int c = tid; c * 8 < K; c += MG_THREADS) {
+    const float4* px = (const float4*)(x + c * 8);
+    const float4 v = px[0], w = px[1];
+    float xv[8] = {v.x, v.y, v.z, v.w, w.x, w.y, w.z, w.w};
+    const u32x4 gq = *(const u32x4*)((const char*)a.g + (size_t)c * 16);
+    float gf[8]; WTr<bf16_t>::unpack(gq, gf);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) xv[e] = (xv[e] - mu) * rs * gf[e];
+    if (a.norm == 0 && a.b) {
+      const u32x4 bq = *(const u32x4*)((const char*)a.b + (size_t)c * 16);
+      float bf[8]; WTr<bf16_t>::unpack(bq, bf);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xv[e] += bf[e];
+    }
+    float4* py = (float4*)(y + c * 8);
+    py[0] = make_float4(xv[0], xv[1], xv[2], xv[3]);
+    py[1] = make_float4(xv[4], xv[5], xv[6], xv[7]);
+  }
+}
+#endif
+
 }  // namespace ppd

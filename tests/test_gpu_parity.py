@@ -273,10 +273,10 @@ def test_speculative_early_prediction_changes_nothing_but_the_traffic(family, k,
 @pytest.mark.gpu
 @pytest.mark.parametrize("name", list(SMALL))
 def test_prompt_in_chunks_is_token_by_token_bit_exact(name, monkeypatch):
-    """ppd_prefill feeds the prompt eight positions at a time (one pass over the weights per chunk, rows of a
+    """ppd_prefill feeds the prompt a chunk of positions at a time (one pass over the weights per chunk, rows of a
     chunk attend causally to each other); every row's arithmetic is that of a one-token pass, so the cache and
     everything decoded from it equal the token-by-token prefill (PPD_PREFILL_CHUNK=1) bit for bit.  Prompt
-    lengths leave ragged last chunks and cross the 64-position attention chunks."""
+    lengths leave ragged last chunks and cross the 64-position attention chunks; the full 16-row chunk as well."""
     cfg = SMALL[name]
     dev = binding.upload_model(pi.make_model(cfg))
 
@@ -290,10 +290,12 @@ def test_prompt_in_chunks_is_token_by_token_bit_exact(name, monkeypatch):
 
     lengths = sorted({2, 3, 9, 10, cfg.n_prompt, min(cfg.max_ctx - 8, 70), min(cfg.max_ctx - 8, 130)})
     got = {n: run(n) for n in lengths}
+    monkeypatch.setenv("PPD_PREFILL_CHUNK", "16")
+    got16 = {n: run(n) for n in lengths}
     monkeypatch.setenv("PPD_PREFILL_CHUNK", "1")
     for n in lengths:
         ref = run(n)
-        for a, b in zip(got[n], ref):
+        for a, b in list(zip(got[n], ref)) + list(zip(got16[n], ref)):
             np.testing.assert_array_equal(np.asarray(a).view(np.uint32) if np.asarray(a).dtype == np.float32 else a,
                                           np.asarray(b).view(np.uint32) if np.asarray(b).dtype == np.float32 else b)
     monkeypatch.delenv("PPD_PREFILL_CHUNK")
