@@ -138,8 +138,8 @@ int ppd_reset(ppd_ctx *ctx);
  * becomes x_0 with match = False.  Implies ppd_reset.  PPD_ECTX if
  * n_prompt > max_ctx; PPD_EINVAL for ids outside [0, vocab).
  * The prompt goes through the decode kernels in chunks of consecutive
- * positions (12 for bf16 weights, 8 for fp32; PPD_PREFILL_CHUNK, at most 16
- * resp. 8): one pass over the weights per chunk, rows of a chunk attending
+ * positions (16 for bf16 weights, 8 for fp32; PPD_PREFILL_CHUNK lowers it):
+ * one pass over the weights per chunk, rows of a chunk attending
  * causally to each other.  Every row's arithmetic is that of a one-token
  * pass, so the cache equals a token-by-token prefill bit for bit
  * (PPD_PREFILL_CHUNK=1 in the environment at ppd_create runs that). */

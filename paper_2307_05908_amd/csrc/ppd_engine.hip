@@ -192,11 +192,9 @@ hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
 }
 
 // rows of a prompt chunk (ppd_prefill feeds the prompt through the decode kernels this many positions at a time:
-// one pass over the weights per chunk instead of per token): up to the 16 columns of an MFMA tile for bf16 models
-// (12 by default: measured fastest on the 7B and 13B shapes, where more rows mean more staging passes per
-// GEMM), the 8 rows of the fp32 GEMM otherwise
+// one pass over the weights per chunk instead of per token): the 16 columns of an MFMA tile for bf16 models,
+// the 8 rows of the fp32 GEMM otherwise
 constexpr int PREFILL_CHUNK = 16;
-constexpr int PREFILL_CHUNK_DEFAULT = 12;
 constexpr int PREFILL_CHUNK_FP32 = 8;
 
 // ---- bf16 models: MFMA GEMM on repacked weights
@@ -220,9 +218,15 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
   // in the fewest passes that fit (same arithmetic, weights still read once).  Launches with a fused
   // norm need whole rows: those fall back to row slices below.
   const int t1 = a.topk > 0 ? (a.NT + c->head_grid - 1) / c->head_grid : (a.NT + 255) / 256;
+  const int tcap = (a.topk > 0 || (ngroups == 1 && !c->in_dual)) ? t1 : t1 * 2;   // tiles per workgroup of this launch shape
   a.passes = c->mg_passes_min;
   if (a.norm >= 0) a.passes = 1;
-  else while (a.passes < 8 && lds_with(mmax, t1 * 2, a.passes) > MG_LDS_MAX) ++a.passes;
+  else while (a.passes < 8 && lds_with(mmax, tcap, a.passes) > MG_LDS_MAX) ++a.passes;
+  {
+    // a pass covers at least one batch of every wave's share: more passes than batches would be empty ones
+    const int nb8 = (a.KT + MG_WAVES - 1) / MG_WAVES, useful = (nb8 + MG_BATCH - 1) / MG_BATCH;
+    if (a.passes > useful) a.passes = useful;
+  }
   a.xrow = mg_xrow_pass(a.KT, a.passes);
   // head launches keep HEAD_MAX_ROWS logits per row where the staged rows were
   if (a.topk > 0 && a.xrow < HEAD_MAX_ROWS * (int)sizeof(float)) a.xrow = HEAD_MAX_ROWS * (int)sizeof(float);
@@ -255,7 +259,6 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
   };
   // rows whose staged form fits LDS
   int mcap = 0;
-  const int tcap = (a.topk > 0 || (ngroups == 1 && !c->in_dual)) ? t1 : t1 * 2;   // tiles per workgroup of this launch shape
   while (mcap < 16 && lds_for(mcap + 1, tcap) <= MG_LDS_MAX) ++mcap;
   if (a.topk > 0 && mmax > mcap) return hipErrorInvalidValue;   // head launches are never cut into row slices
   if (mmax <= mcap) return go(a, ngroups, mmax);
@@ -724,7 +727,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   c->skew = env_int("PPD_SKEW", 0) == 1;
   {
     const int cap = d.wdtype == 1 ? PREFILL_CHUNK : PREFILL_CHUNK_FP32;
-    c->prefill_chunk = env_int("PPD_PREFILL_CHUNK", d.wdtype == 1 ? PREFILL_CHUNK_DEFAULT : cap);
+    c->prefill_chunk = env_int("PPD_PREFILL_CHUNK", cap);
     if (c->prefill_chunk > cap) c->prefill_chunk = cap;
   }
   c->gmax1 = env_int("PPD_GMAX1", 512);

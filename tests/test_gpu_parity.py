@@ -199,8 +199,10 @@ def test_ffn_in_burst_timing_invalidates_the_sequence():
 @pytest.mark.parametrize("family", ["llama", "opt"])
 def test_staging_in_passes_is_bit_identical(family, monkeypatch):
     """Rows too long for LDS are staged in several passes with the accumulators parked in between; forced on
-    here (PPD_MGPASSES), every token and logit equals the single-pass run bit for bit."""
-    cfg = small_cfg(family)
+    here (PPD_MGPASSES), every token and logit equals the single-pass run bit for bit.  The feed-forward width
+    is large enough (2056: nine 32-column blocks per wave, the last one ragged) for every forced pass to carry
+    part of the reduction."""
+    cfg = small_cfg(family, d_ff=2056)
     dev = binding.upload_model(pi.make_model(cfg))
     prompt = pi.make_prompt(cfg)
 
