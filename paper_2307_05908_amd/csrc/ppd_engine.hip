@@ -483,6 +483,12 @@ int set_state(ppd_ctx* c, int pos, int tok, int take_next = 0) {
 int run_head(ppd_ctx* c, bool early, bool adopt) {
   const ppd_model_dims& d = c->d;
   const bool spec = c->spec && adopt && !early;
+  // top-k sampling with few kept tokens is drawn from the head's block lists inside the selection kernel;
+  // other sampling goes through the sampling kernel
+  const int ks_fast = (!early && c->samp_mode == 1 && c->samp_k <= MAXM) ? (c->samp_k < d.vocab ? c->samp_k : d.vocab) : 0;
+  const bool samp_kernel = !early && c->samp_mode && !ks_fast;
+  int topk = (early || spec) ? c->k : 1;
+  if (ks_fast > topk) topk = ks_fast;
   {
     GemmArgs a; memset(&a, 0, sizeof a);
     GemmGroup& G = a.g[0];
@@ -491,7 +497,7 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     G.ng = c->lnf_g; G.nb = d.norm == 0 ? c->lnf_b : nullptr; G.M = spec ? 1 + c->k : 1;
     a.K = d.d_model; a.N[0] = d.vocab; a.ntot = d.vocab; a.ldx = d.d_model; a.ldy = d.vocab;
     a.norm = d.norm; a.eps = d.norm_eps; a.act = 0;
-    a.topk = (early || spec) ? c->k : 1; a.pk_val = c->pk_val; a.pk_idx = c->pk_idx;
+    a.topk = topk; a.pk_val = c->pk_val; a.pk_idx = c->pk_idx;
     ProfScope ps(c, PPD_KC_HEAD);
     if (c->mfma) {
       void* P[2] = {(early && c->early_p) ? c->early_p : c->head_p, nullptr};
@@ -499,7 +505,7 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     } else
     HIPCHK(c, launch_gemm(c, a, 1, false));
   }
-  if (!early && c->samp_mode) {
+  if (samp_kernel) {
     SampleArgs sa; memset(&sa, 0, sizeof sa);
     sa.z = c->logits; sa.n = d.vocab; sa.mode = c->samp_mode; sa.ks = c->samp_k; sa.p = c->samp_p; sa.seed = c->samp_seed;
     sa.ds = c->ds; sa.w = c->samp_w; sa.keys = c->samp_keys; sa.npad = c->samp_npad;
@@ -509,8 +515,8 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
     HIPCHK(c, hipGetLastError());
   }
   SelectArgs s; memset(&s, 0, sizeof s);
-  s.sampled = (!early && c->samp_mode) ? 1 : 0;
-  s.pk_val = c->pk_val; s.pk_idx = c->pk_idx; s.nblk = c->head_grid; s.kk = (early || spec) ? c->k : 1;
+  s.sampled = samp_kernel ? 1 : 0; s.samp_topk = ks_fast; s.samp_seed = c->samp_seed;
+  s.pk_val = c->pk_val; s.pk_idx = c->pk_idx; s.nblk = c->head_grid; s.kk = topk;
   s.pk_stride = (int)c->pk_slots;
   s.k = adopt || early ? c->k : 0; s.mode = early ? 0 : 1; s.ds = c->ds; s.host_result = c->host_result_dev;
   dim3 grid(1, 1);

@@ -911,6 +911,10 @@ struct SelectArgs {
                             // the next position, in the half that position's parity selects
   int vocab;
   int sampled;              // mode 1: the final prediction is ds->sampled (drawn by sample_kernel), not the arg max
+  // mode 1, top-k sampling with samp_topk <= kk kept tokens: they are the head of the merged block lists, so the
+  // draw happens here (fp64 inversion over the samp_topk best in ranking order, same uniform as sample_kernel)
+  int samp_topk;
+  uint64_t samp_seed;
 };
 // ------------------------------------------------------------------ sampling-based final prediction
 // Appendix B: the final prediction is drawn by top-k or top-p sampling instead of the arg max; the rest of a
@@ -924,6 +928,18 @@ struct SelectArgs {
 // u W") asks for the largest key kappa whose mass-at-or-above G(kappa) meets a bound; G is evaluated in full, in
 // one fixed order of additions, for one trial key per pass (so it is monotone in the key whatever the rounding),
 // and kappa is fixed bit by bit from the top of an order-preserving 32-bit image of the logit.
+// ten rounds: two 32x32->64 products, halves crossed over and mixed with counter and key; key steps by the Weyl constants
+__device__ inline uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+  for (int r = 0; r < 10; ++r) {
+    if (r) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+    c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+  }
+  return c0;
+}
+
 #ifdef PPD_ENGINE_TU
 constexpr int SAMP_THREADS = 1024;
 constexpr int SAMP_MEMU = 8;     // loads in flight per thread when the logits are re-read from memory
@@ -945,18 +961,6 @@ __device__ inline uint32_t samp_key(float z) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 __device__ inline float samp_unkey(uint32_t k) { return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k); }
-
-// ten rounds: two 32x32->64 products, halves crossed over and mixed with counter and key; key steps by the Weyl constants
-__device__ inline uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
-  for (int r = 0; r < 10; ++r) {
-    if (r) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
-    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
-    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
-    const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
-    c0 = n0; c1 = l1; c2 = n2; c3 = l0;
-  }
-  return c0;
-}
 
 template <int CTRL> __device__ __forceinline__ double dpp_f64(double v) {
   const long long b = __double_as_longlong(v);
@@ -1165,7 +1169,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   __shared__ float wv[SEL_THREADS / WAVE];
   __shared__ int wi[SEL_THREADS / WAVE];
   __shared__ int win[MAXM];
-  __shared__ int s_midx;
+  __shared__ float winv[MAXM];
+  __shared__ int s_midx, s_tok;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // merge of one row's block lists: the best nk by (value descending, id ascending) land in win[]
   auto merge_row = [&](int prow, int nk) {
@@ -1202,7 +1207,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
 #pragma unroll
     for (int w = 1; w < SEL_THREADS / WAVE; ++w) if (better(wv[w], wi[w], wv[bw], wi[bw])) bw = w;
     const int wid = wi[bw];
-    if (tid == 0) win[r] = wid;
+    if (tid == 0) { win[r] = wid; winv[r] = wv[bw]; }
     int cur = 0x7fffffff;
 #pragma unroll
     for (int q = 0; q < MAXM; ++q) if (q == head) cur = li[q];
@@ -1210,7 +1215,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   }
   __syncthreads();
   };
-  merge_row(0, a.mode == 0 ? a.k : 1);
+  merge_row(0, a.mode == 0 ? a.k : (a.samp_topk > 0 ? a.samp_topk : 1));
   if (a.mode == 0) {
     // candidates and their rows; block x handles row blockIdx.y
     if (blockIdx.x == 0 && blockIdx.y == 0 && tid < a.k) a.ds->cand[tid] = win[tid];
@@ -1226,7 +1231,20 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
     return;
   }
   // final: verification
-  const int token = a.sampled ? a.ds->sampled : win[0];
+  if (a.samp_topk > 0) {
+    if (tid == 0) {
+      const uint32_t word = philox4x32_10_word0((uint32_t)(a.ds->pos + 1), 0u, 0u, 0u, (uint32_t)(a.samp_seed & 0xffffffffu), (uint32_t)(a.samp_seed >> 32));
+      const double u = (double)(word >> 8) * (1.0 / 16777216.0);
+      double cum[MAXM], acc = 0.0;
+      for (int r = 0; r < a.samp_topk; ++r) { acc += exp((double)winv[r] - (double)winv[0]); cum[r] = acc; }
+      const double target = u * acc;
+      int pick = a.samp_topk - 1;
+      for (int r = a.samp_topk - 1; r >= 0; --r) if (cum[r] > target) pick = r;
+      s_tok = win[pick];
+    }
+    __syncthreads();
+  }
+  const int token = a.samp_topk > 0 ? s_tok : (a.sampled ? a.ds->sampled : win[0]);
   if (tid == 0) {
     int midx = -1;
     for (int q = 0; q < a.k; ++q) if (a.ds->cand[q] == token) { midx = q; break; }
