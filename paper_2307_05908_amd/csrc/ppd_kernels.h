@@ -1063,24 +1063,51 @@ __global__ __launch_bounds__(SAMP_THREADS) void sample_kernel(SampleArgs a) {
   // ---- the largest key kappa with G(kappa) >= T (kind 0), G(kappa) > T (kind 1) or count(kappa) >= K (kind 2);
   // the bound holds at the smallest key present, so kappa >= 1.  Also the mass and count strictly above kappa
   // and the number of tokens at kappa.
+  double S; int n_all;
+  G(1u, S, n_all);
+  // The keys still in question after bit b are those that agree with the prefix above b; once a single token
+  // is left (count at the prefix minus count above the bucket), its key is kappa and the remaining bits need
+  // no passes: the mass and count above the bucket are the ones already found.
   auto search = [&](int kind, double T, int K, uint32_t& kappa, double& above, int& nabove, int& ties) {
     uint32_t pre = 0u;
-    int c_at = 0;
-    for (int bit = 31; bit >= 0; --bit) {
+    int c_at = n_all, c_hi = 0, bit = 31;
+    double g_hi = 0.0;
+    bool single = c_at - c_hi == 1;
+    for (; bit >= 0 && !single; --bit) {
       const uint32_t t = pre | (1u << bit);
       double g; int c;
       G(t, g, c);
       const bool ok = kind == 0 ? g >= T : (kind == 1 ? g > T : c >= K);
       if (ok) { pre = t; c_at = c; }
+      else { c_hi = c; g_hi = g; }
+      single = c_at - c_hi == 1;
+    }
+    if (single) {
+      // bits above `bit` are fixed (the loop has already stepped past the last one it tried)
+      const int sh = bit + 1;
+      __syncthreads();
+      if (REG) {
+#pragma unroll
+        for (int e = 0; e < VPT; ++e) {
+          const uint32_t k = key[e * KS];
+          if (k && (sh >= 32 || (k >> sh) == (pre >> sh))) s_prefix = k;
+        }
+      } else {
+        for (int i = tid; i < a.npad; i += SAMP_THREADS) {
+          const uint32_t k = a.keys[i];
+          if (k && (sh >= 32 || (k >> sh) == (pre >> sh))) s_prefix = k;
+        }
+      }
+      __syncthreads();
+      kappa = s_prefix; above = g_hi; nabove = c_hi; ties = 1;
+      __syncthreads();
+      return;
     }
     kappa = pre;
     above = 0.0; nabove = 0;
     if (kappa != 0xffffffffu) G(kappa + 1u, above, nabove);
     ties = c_at - nabove;
   };
-
-  double S; int n_all;
-  G(1u, S, n_all);
   const int pos_new = a.ds->pos + 1;
   const uint32_t word = philox4x32_10_word0((uint32_t)pos_new, 0u, 0u, 0u, (uint32_t)(a.seed & 0xffffffffu), (uint32_t)(a.seed >> 32));
   const double u = (double)(word >> 8) * (1.0 / 16777216.0);
