@@ -72,7 +72,7 @@ struct ppd_ctx {
   float2 *rope;          // [max_ctx][hd/2]
   DevState *ds;
   int32_t *prompt_dev;   // [max_ctx]
-  int32_t *host_result;  // pinned, 2 ints
+  int32_t *host_result;  // pinned: token, match index, the round's candidates
   int32_t *host_result_dev; // the same memory as the GPU sees it
   // captured rounds: 0 ppd round from layer 1, 1 ppd round after a match, 2 plain step
   int use_graphs;
@@ -471,7 +471,7 @@ int run_embed(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos_of
 }
 
 int set_state(ppd_ctx* c, int pos, int tok, int take_next = 0) {
-  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->cur, c->ds, pos, tok, take_next);
+  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->cur, c->ds, pos, tok, take_next, c->host_result_dev + 2);
   HIPCHK(c, hipGetLastError());
   return PPD_OK;
 }
@@ -775,7 +775,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   alloc((void**)&c->ds, sizeof(DevState));
   alloc((void**)&c->prompt_dev, (size_t)d.max_ctx * sizeof(int32_t));
   if (d.pos == 1) alloc((void**)&c->rope, (size_t)d.max_ctx * (d.head_dim / 2) * sizeof(float2));
-  if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, 2 * sizeof(int32_t), hipHostMallocMapped);
+  if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, (2 + MAXM) * sizeof(int32_t), hipHostMallocMapped);
   if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&c->host_result_dev, c->host_result, 0);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking);
@@ -939,9 +939,7 @@ int ppd_step(ppd_ctx* c, int32_t* out_tokens, int max_out, ppd_step_info* info) 
   out_tokens[0] = tok;
   if (info) {
     info->token = tok; info->matched = c->matched; info->match_idx = midx;
-    int32_t cand[MAXM];
-    HIPCHK(c, hipMemcpy(cand, c->ds->cand, sizeof cand, hipMemcpyDeviceToHost));
-    for (int i = 0; i < PPD_MAX_K; ++i) info->cand[i] = i < c->k ? cand[i] : -1;
+    for (int i = 0; i < PPD_MAX_K; ++i) info->cand[i] = i < c->k ? c->host_result[2 + i] : -1;   // (pinned memory, written by the round)
   }
   return 1;
 }

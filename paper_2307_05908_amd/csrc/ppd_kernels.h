@@ -141,9 +141,14 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* p, size_t
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) *sink = acc.x;   // keeps the loads alive; practically never taken
 }
 // take_next: the round about to start uses the candidates the previous round predicted for it
-__global__ void set_state_kernel(DevState* ds, int pos, int tok, int take_next) {
+// (host_cand: the candidates' copy in pinned host memory, for the round's record)
+__global__ void set_state_kernel(DevState* ds, int pos, int tok, int take_next, int32_t* host_cand) {
   if (threadIdx.x == 0) { ds->pos = pos; if (tok >= 0) ds->next_tok = tok; }
-  if (take_next && threadIdx.x < MAXM) ds->cand[threadIdx.x] = ds->cand_next[threadIdx.x];
+  if (take_next && threadIdx.x < MAXM) {
+    const int32_t c = ds->cand_next[threadIdx.x];
+    ds->cand[threadIdx.x] = c;
+    host_cand[threadIdx.x] = c;
+  }
 }
 #endif
 
@@ -892,7 +897,7 @@ struct SelectArgs {
   int k;
   int mode;             // 0: early top-k -> cand[0..k) + embed; 1: final arg max + verify + adopt
   DevState* ds;
-  int32_t* host_result; // device-visible pinned host memory: [0] token, [1] match_idx (mode 1)
+  int32_t* host_result; // device-visible pinned host memory: [0] token, [1] match_idx (mode 1), [2..2+k) candidates (mode 0)
   EmbedArgs emb;        // candidate rows (mode 0)
   // adoption (mode 1)
   float* h;                 // [1+k][d_model]: row 0 main, rows 1.. candidates
@@ -1245,7 +1250,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   merge_row(0, a.mode == 0 ? a.k : (a.samp_topk > 0 ? a.samp_topk : 1));
   if (a.mode == 0) {
     // candidates and their rows; block x handles row blockIdx.y
-    if (blockIdx.x == 0 && blockIdx.y == 0 && tid < a.k) a.ds->cand[tid] = win[tid];
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid < a.k) { a.ds->cand[tid] = win[tid]; a.host_result[2 + tid] = win[tid]; }
     const int r = blockIdx.y;
     EmbedArgs e = a.emb;
     int tok = win[r];
