@@ -891,6 +891,8 @@ __global__ __launch_bounds__(MERGE_THREADS) void attn_merge_kernel(MergeArgs a) 
 // early candidates ("if x-hat^(PID) = x_{t+1}"), then adoption: on a match the matching candidate's
 // hidden row becomes the main row and its key/value tails of layers 1..d-dbar become cache position
 // t+1; without a match nothing is copied and the tails are overwritten by the next round.
+// Appendix B's sampling-based variants replace only the arg max: the token verified here is then the one
+// drawn by top-k sampling (inside this kernel, from the merged lists) or by the sampling kernel (top-p).
 struct SelectArgs {
   const float* pk_val; const int32_t* pk_idx;   // [nblk][MAXM] block candidates, first kk of each valid
   int nblk; int kk;     // kk = k (early) or 1 (final)
