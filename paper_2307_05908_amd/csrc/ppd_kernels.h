@@ -1484,11 +1484,11 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
     return (s < nb && col < K) ? col : -1;
   };
   auto dma_pass = [&](int pass) {
-    for (int m = 0; m < M; ++m)
-      for (int u = wave; u < nbp_; u += MG_WAVES) {
-        const int col = pass_col(pass, u * 256 + lane * 4);
-        if (col >= 0) dma16(G.X + (size_t)m * a.ldx + col, lds + off_x + m * xrow + u * 1024);
-      }
+    for (int u = wave; u < nbp_; u += MG_WAVES) {
+      const int col = pass_col(pass, u * 256 + lane * 4);      // (the same for every row)
+      if (col >= 0)
+        for (int m = 0; m < M; ++m) dma16(G.X + (size_t)m * a.ldx + col, lds + off_x + m * xrow + u * 1024);
+    }
   };
   {
     if (MP && npass > 1) dma_pass(0);
@@ -1643,6 +1643,32 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_kernel(MGemmArgs a) {
   // (with passes: the same split, for the runs of one pass; chunks outside every wave's share become zeros)
   auto convert_rows = [&](int pass) {
   const int nch = (MP && npass > 1) ? nbp_ * 32 : nchunk;
+  if constexpr (MP) {
+    if (npass > 1) {
+      // (no fused norm with passes; whether a chunk lies inside a wave's share is the same for every row)
+      for (int c = tid; c < nch; c += MG_THREADS) {
+        const bool inside = pass_col(pass, c * 8) >= 0;
+        for (int m = 0; m < M; ++m) {
+          char* px = lds + off_x + m * xrow + c * 32;
+          float xv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          if (inside) {
+            const float4 v = ((const float4*)px)[0], w = ((const float4*)px)[1];
+            xv[0] = v.x; xv[1] = v.y; xv[2] = v.z; xv[3] = v.w; xv[4] = w.x; xv[5] = w.y; xv[6] = w.z; xv[7] = w.w;
+          }
+          uint32_t hp[4], lp[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            hp[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){xv[2 * e], xv[2 * e + 1]}, bf16x2));
+            const float r0 = xv[2 * e] - __uint_as_float(hp[e] << 16), r1 = xv[2 * e + 1] - __uint_as_float(hp[e] & 0xffff0000u);
+            lp[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){r0, r1}, bf16x2));
+          }
+          ((uint4*)px)[0] = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+          ((uint4*)px)[1] = make_uint4(lp[0], lp[1], lp[2], lp[3]);
+        }
+      }
+      return;
+    }
+  }
   for (int m = 0; m < M; ++m) {
     const float mu = a.norm >= 0 ? stat[m] : 0.f, rs = a.norm >= 0 ? stat[16 + m] : 1.f;
     for (int c = tid; c < nch; c += MG_THREADS) {
