@@ -178,6 +178,27 @@ def test_llama7b_speculative_early_prediction_full_config(monkeypatch):
     assert sb["weight_bytes"] - sa["weight_bytes"] == follow * cfg.head_weight_bytes()
 
 
+def test_llama7b_prompt_chunks_full_config(monkeypatch):
+    """Prompt chunks at the 7B shape's own widths (16 rows staged in 2, 4 and 6 passes by the four GEMMs of a
+    layer, causal attention over two 64-position chunks): the cache equals the token-by-token prefill's, so the
+    rounds decoded from it are the same bit for bit."""
+    cfg, m, dev = model_on_gpu("llama7b")
+    prompt = pi.make_prompt(cfg, 100)
+
+    def run():
+        P = binding.PPD(cfg, dev, k=3)
+        toks, z, _ = gpu_generate(P, prompt, 4, "ppd")
+        P.close()
+        return toks, z
+
+    t16, z16 = run()
+    monkeypatch.setenv("PPD_PREFILL_CHUNK", "1")
+    t1, z1 = run()
+    monkeypatch.delenv("PPD_PREFILL_CHUNK")
+    np.testing.assert_array_equal(t16, t1)
+    np.testing.assert_array_equal(z16.view(np.uint32), z1.view(np.uint32))
+
+
 @pytest.mark.parametrize("name", ["llama7b_a1", "llama7b_a0p1", "llama7b_a0p02"])
 def test_llama7b_controlled_match_rate(name):
     if not os.path.exists(os.path.join(GOLD, name + ".npz")):
