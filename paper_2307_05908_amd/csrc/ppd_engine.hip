@@ -65,6 +65,7 @@ struct ppd_ctx {
   int last_kind;
   // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
   int prefill_chunk;
+  int dev_pos_pending;   // host mirror of the device state's pending position (-1: unknown)
   float* xn;      // [rows][d_model] normalised rows of a prompt chunk (norm_rows_kernel)
   int samp_mode, samp_k; double samp_p; uint64_t samp_seed;
   double* samp_w; uint32_t* samp_keys; int samp_npad;   // scratch of the sampling kernel
@@ -470,9 +471,10 @@ int run_embed(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int pos_of
   return PPD_OK;
 }
 
-int set_state(ppd_ctx* c, int pos, int tok, int take_next = 0) {
-  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->cur, c->ds, pos, tok, take_next, c->host_result_dev + 2);
+int set_state(ppd_ctx* c, int pos, int tok) {
+  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, c->cur, c->ds, pos, tok);
   HIPCHK(c, hipGetLastError());
+  c->dev_pos_pending = pos;
   return PPD_OK;
 }
 
@@ -549,6 +551,8 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
 int issue_round(ppd_ctx* c, int kind, int pmax) {
   const int d = c->d.n_layers, dbar = c->dbar, nb = c->nb, k = c->k;
   int rc;
+  hipLaunchKernelGGL(begin_round_kernel, dim3(1), dim3(64), 0, c->cur, c->ds, kind == 3 ? 1 : 0, c->host_result_dev + 2);
+  HIPCHK(c, hipGetLastError());
   if (kind == 2) {
     if ((rc = run_embed(c, &c->ds->next_tok, 1, 0, 0))) return rc;
     for (int l = 0; l < d; ++l) {
@@ -613,7 +617,8 @@ int run_round(ppd_ctx* c, int kind, int pos) {
   int rc;
   HIPCHK(c, hipEventRecord(c->join_ev, c->user_stream));
   HIPCHK(c, hipStreamWaitEvent(c->stream, c->join_ev, 0));
-  if ((rc = set_state(c, pos, -1, kind == 3))) return rc;
+  // the device already holds this position as pending when the previous call was a round at pos - 1
+  if (c->dev_pos_pending != pos && (rc = set_state(c, pos, -1))) return rc;
   const int pmax = pos + (kind == 2 ? 0 : 1);
   if (c->use_graphs && !c->prof) {
     const int nchunks = pmax / ATT_CHUNK + 1;
@@ -638,7 +643,9 @@ int run_round(ppd_ctx* c, int kind, int pos) {
   } else {
     if ((rc = issue_round(c, kind, pmax))) return rc;
   }
+  c->dev_pos_pending = -1;                       // (unknown until the round is known to have run)
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->dev_pos_pending = pos + 1;                  // left by the round's final selection
   if (c->prof) prof_collect(c);
   return PPD_OK;
 }
@@ -712,6 +719,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   if (!c) return PPD_ENOMEM;
   c->d = d; c->k = k; c->dbar = exit_layer; c->nb = d.n_layers - exit_layer;
   c->user_stream = (hipStream_t)hip_stream;
+  c->dev_pos_pending = -1;
   c->wbytes = d.wdtype == 0 ? 4 : 2;
   c->tok_emb = w->tok_emb; c->pos_emb = w->pos_emb; c->lnf_g = w->lnf_g; c->lnf_b = w->lnf_b;
   c->lm_head = w->lm_head; c->early_head = w->early_head;
@@ -870,7 +878,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
 int ppd_reset(ppd_ctx* c) {
   if (!c) return PPD_EINVAL;
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  c->n_ctx = -1; c->matched = 0; c->finished = 0; c->have_early = 0;
+  c->n_ctx = -1; c->matched = 0; c->finished = 0; c->have_early = 0; c->dev_pos_pending = -1;
   memset(&c->st, 0, sizeof c->st);
   return PPD_OK;
 }

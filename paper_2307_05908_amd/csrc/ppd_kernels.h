@@ -46,6 +46,7 @@ struct DevState {
   int32_t cand[MAXM]; // early top-k ids
   int32_t cand_next[MAXM]; // candidates of the next round, predicted at the end of a matching round
   int32_t sampled;    // final prediction drawn by the sampling kernel (sampling-based variants)
+  int32_t pos_pending; // position of the next round: set explicitly, or left by a round's final selection (pos + 1)
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
@@ -141,9 +142,14 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* p, size_t
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) *sink = acc.x;   // keeps the loads alive; practically never taken
 }
 // take_next: the round about to start uses the candidates the previous round predicted for it
+__global__ void set_state_kernel(DevState* ds, int pos, int tok) {
+  if (threadIdx.x == 0) { ds->pos = pos; ds->pos_pending = pos; if (tok >= 0) ds->next_tok = tok; }
+}
+// First launch of every round: the position the previous round (or set_state_kernel) left pending becomes the
+// current one; take_next: the round uses the candidates the previous round predicted for it
 // (host_cand: the candidates' copy in pinned host memory, for the round's record)
-__global__ void set_state_kernel(DevState* ds, int pos, int tok, int take_next, int32_t* host_cand) {
-  if (threadIdx.x == 0) { ds->pos = pos; if (tok >= 0) ds->next_tok = tok; }
+__global__ void begin_round_kernel(DevState* ds, int take_next, int32_t* host_cand) {
+  if (threadIdx.x == 0) ds->pos = ds->pos_pending;
   if (take_next && threadIdx.x < MAXM) {
     const int32_t c = ds->cand_next[threadIdx.x];
     ds->cand[threadIdx.x] = c;
@@ -1288,6 +1294,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   const int midx = s_midx;
   if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) {
     a.ds->result[0] = token; a.ds->result[1] = midx; a.ds->next_tok = token;
+    a.ds->pos_pending = a.ds->pos + 1;      // the next round's position (its first launch takes it over)
     a.host_result[0] = token; a.host_result[1] = midx;
   }
   if (midx < 0 || a.nb == 0) return;
