@@ -123,7 +123,11 @@ enum {
  * (exit_layer, 1-based: the early prediction reads the output of that layer,
  * ceil(d/2) <= exit_layer <= d-1 as Theorem 4.1 requires dbar >= d/2), k.
  * dims, w: HOST structs, copied.  hip_stream: a hipStream_t (NULL = the
- * default stream); all work of this context is issued on it.  The KV cache,
+ * default stream), the caller's: the context runs on streams of its own and
+ * makes them wait, at every ppd_prefill, for what the caller has queued on
+ * hip_stream until then (the weights must be complete in device memory by
+ * then; they are read again at every step and must not change).  Every call
+ * is synchronous: the context's streams are idle on return.  The KV cache,
  * the candidates' KV tails and all scratch are allocated here (device
  * memory, freed by ppd_destroy).  *out receives the context (HOST). */
 int ppd_create(const ppd_model_dims *dims, const ppd_weights *w, int k, int exit_layer,

@@ -615,8 +615,8 @@ int issue_round(ppd_ctx* c, int kind, int pmax) {
 // wait, read token and match index from pinned memory.
 int run_round(ppd_ctx* c, int kind, int pos) {
   int rc;
-  HIPCHK(c, hipEventRecord(c->join_ev, c->user_stream));
-  HIPCHK(c, hipStreamWaitEvent(c->stream, c->join_ev, 0));
+  // (work the caller queued on its stream before ppd_prefill -- the weights -- was waited for there; a round
+  // reads nothing else of the caller's)
   // the device already holds this position as pending when the previous call was a round at pos - 1
   if (c->dev_pos_pending != pos && (rc = set_state(c, pos, -1))) return rc;
   const int pmax = pos + (kind == 2 ? 0 : 1);
