@@ -163,6 +163,9 @@ class PPD:
         self._h = h
         self._tok = np.zeros(4, dtype=np.int32)
         self._logits = np.zeros(cfg.vocab, dtype=np.float32)
+        # looked up once: the step calls are made thousands of times per second
+        self._tok_ptr = self._tok.ctypes.data
+        self._fn_step, self._fn_plain = lib.ppd_step, lib.plain_greedy_step
 
     def _chk(self, rc: int, what: str) -> int:
         if rc < 0:
@@ -190,12 +193,15 @@ class PPD:
     def ppd_step(self, want_info: bool = True):
         """One round.  Returns (token or None after EOS, StepInfo or None)."""
         info = StepInfo() if want_info else None
-        n = self._chk(load_library().ppd_step(self._h, self._tok.ctypes.data, 1,
-                                              ctypes.byref(info) if want_info else None), "ppd_step")
+        n = self._fn_step(self._h, self._tok_ptr, 1, ctypes.byref(info) if want_info else None)
+        if n < 0:
+            self._chk(n, "ppd_step")
         return (int(self._tok[0]) if n == 1 else None), info
 
     def plain_greedy_step(self):
-        n = self._chk(load_library().plain_greedy_step(self._h, self._tok.ctypes.data), "plain_greedy_step")
+        n = self._fn_plain(self._h, self._tok_ptr)
+        if n < 0:
+            self._chk(n, "plain_greedy_step")
         return int(self._tok[0]) if n == 1 else None
 
     def ppd_get_logits(self) -> np.ndarray:
