@@ -637,8 +637,9 @@ struct AttnArgs {
 };
 
 template <int HD> __host__ __device__ constexpr int attn_lds_floats(int M) {
-  // raw q|k|v, then q (scaled), own k, own v, scores, statistics (max, sum, own weight, -), wave partials
-  return M * (3 * HD + 3 * HD + ATT_CHUNK + 4 + ATT_WAVES * HD);
+  // raw q|k|v and, later, the wave partials in the same place (the raw rows are done with after the rotation),
+  // then q (scaled), own k, own v, scores, statistics (max, sum, own weight, -)
+  return M * (ATT_WAVES * HD + 3 * HD + ATT_CHUNK + 4);
 }
 
 template <int HD, bool CAUSAL = false>
@@ -657,13 +658,14 @@ __global__ __launch_bounds__(ATT_THREADS) void attn_kernel(AttnArgs a) {
   auto pos_of = [&](int m) { return CAUSAL ? p + m : p; };
   auto owns = [&](int m) { const int pm = pos_of(m); return pm >= j0 && pm < j0 + ATT_CHUNK; };
   auto live = [&](int m) { return !CAUSAL || j0 <= pos_of(m); };
+  static_assert(ATT_WAVES >= 3, "the wave partials reuse the raw rows' place");
   float* raw = lds;                   // [M][3][HD]
-  float* qs = raw + M * 3 * HD;       // [M][HD]
+  float* ored = lds;                  // [ATT_WAVES][M][HD], written only after the barriers that follow the rotation
+  float* qs = lds + M * ATT_WAVES * HD;   // [M][HD]
   float* ko = qs + M * HD;            // [M][HD]
   float* vo = ko + M * HD;            // [M][HD]
   float* sc = vo + M * HD;            // [M][ATT_CHUNK]
   float* st = sc + M * ATT_CHUNK;     // [M][4]
-  float* ored = st + M * 4;           // [ATT_WAVES][M][HD]
 
   // own q, k, v of every row, as they are: kilobyte pieces of the [M][3][HD] image
   {
