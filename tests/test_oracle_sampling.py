@@ -118,3 +118,35 @@ def test_ppd_with_sampling_draws_the_tokens_of_plain_sampling(family, mode, ks, 
     assert not np.array_equal(o.plain_greedy(prompt, 10), plain)
     o.set_selection(oracle.GREEDY)
     np.testing.assert_array_equal(o.plain_greedy(prompt, 10), greedy)
+
+
+def test_sampler_invariants_on_random_inputs():
+    """Properties that hold for every input: the draw lies in the kept set; it does not move when a constant
+    is added to all logits (large ones included: no overflow in the weights); it walks down the ranking as u
+    grows; top-k sampling with everything kept is top-p sampling with p = 1."""
+    rng = np.random.default_rng(5)
+    for trial in range(60):
+        n = int(rng.integers(2, 300))
+        z = rng.standard_normal(n) * float(rng.choice([0.1, 1.0, 8.0]))
+        if trial % 3 == 0:
+            z[rng.integers(0, n, size=n // 2)] = z[0]            # ties
+        order = np.lexsort((np.arange(n), -z))
+        rank = np.empty(n, dtype=int)
+        rank[order] = np.arange(n)
+        ks = int(rng.integers(1, n + 1))
+        p = float(rng.uniform(0.05, 1.0))
+        prob = softmax(z)[order]
+        m_p = int(np.searchsorted(np.cumsum(prob), p * (1 - 1e-12))) + 1
+        last = {}
+        for u in np.linspace(0.0, 0.9999, 23):
+            tk = oracle.sample(z, oracle.TOP_K, ks, 1.0, u)
+            tp = oracle.sample(z, oracle.TOP_P, 0, p, u)
+            assert rank[tk] < ks
+            assert rank[tp] < min(m_p + 1, n)                    # (+1: p S may fall on a cumulative sum's rounding)
+            for shift in (1000.0, -1000.0):
+                assert oracle.sample(z + shift, oracle.TOP_K, ks, 1.0, u) == tk
+                assert oracle.sample(z + shift, oracle.TOP_P, 0, p, u) == tp
+            for name, t in (("k", tk), ("p", tp)):
+                assert rank[t] >= last.get(name, 0)
+                last[name] = rank[t]
+            assert oracle.sample(z, oracle.TOP_K, n, 1.0, u) == oracle.sample(z, oracle.TOP_P, 0, 1.0, u)
