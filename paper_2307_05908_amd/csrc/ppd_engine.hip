@@ -26,7 +26,7 @@ struct LayerW {
 struct ppd_ctx {
   ppd_model_dims d;
   int k, dbar, nb;   // nb = d - dbar: layers each candidate runs, = pipelined steps per round
-  hipStream_t user_stream;   // the caller's stream: work of a call is ordered after what it holds
+  hipStream_t user_stream;   // the caller's stream: ppd_prefill orders the context's work after what it holds
   hipStream_t stream;        // the context's own stream: every launch goes here (a graph cannot be captured on the null stream)
   hipStream_t stream2;       // second stream: the candidates' layers of the parallel phase run here, next to the main token's
   hipStream_t cur;           // stream the launch helpers issue to
@@ -46,13 +46,14 @@ struct ppd_ctx {
   void *head_p, *early_p;
   std::vector<void*> owned;   // every repacked buffer, for ppd_destroy
   // device memory owned by the context
-  char *Kc, *Vc;         // [L][H][max_ctx][hd]
+  char *Kc, *Vc;         // [L][H][16-position blocks][hd/16][64][4] fp32 (see k_index / v_index)
   char *tailK, *tailV;   // [nb][k][H][hd]
-  float *h;              // [1+k][d_model]  row 0: main token, rows 1..k: candidates
-  float *qkv;            // [1+k][3*d_model]
-  float *att;            // [1+k][d_model]
-  float *ffn;            // [1+k][d_ff]
-  float *part;           // [1+k][H][nchunk_max][hd+2]
+  // activation rows: max(1 + k, rows of a prompt chunk); row 0: main token, rows 1..k: candidates
+  float *h;              // [rows][d_model]
+  float *qkv;            // [rows][3*d_model]
+  float *att;            // [rows][d_model]
+  float *ffn;            // [rows][d_ff]
+  float *part;           // [rows][H][nchunk_max][hd+2]
   float *logits, *early_logits;  // [1 + k][vocab] (row 0: the main token's), [vocab]
   float *early_spec;             // [2][vocab] early logits predicted at the end of the previous round (spec)
   float *pk_val; int32_t *pk_idx; // [1 + k][pk_slots][MAXM] block top-k candidates of the head GEMM, per row
@@ -62,11 +63,11 @@ struct ppd_ctx {
   // then runs on all 1 + k rows; after a match the matching row's top-k are the next candidates and the
   // next round (kind 3) starts with its parallel phase: one head pass per matching round instead of two.
   int spec;
-  int last_kind;
-  // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
-  int prefill_chunk;
+  int last_kind;         // kind of the last round (which buffer holds its early logits)
+  int prefill_chunk;     // prompt positions per chunk
   int dev_pos_pending;   // host mirror of the device state's pending position (-1: unknown)
-  float* xn;      // [rows][d_model] normalised rows of a prompt chunk (norm_rows_kernel)
+  float* xn;             // [rows][d_model] normalised rows of a prompt chunk (norm_rows_kernel)
+  // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
   int samp_mode, samp_k; double samp_p; uint64_t samp_seed;
   double* samp_w; uint32_t* samp_keys; int samp_npad;   // scratch of the sampling kernel
   int head_grid;
@@ -75,10 +76,11 @@ struct ppd_ctx {
   int32_t *prompt_dev;   // [max_ctx]
   int32_t *host_result;  // pinned: token, match index, the round's candidates
   int32_t *host_result_dev; // the same memory as the GPU sees it
-  // captured rounds: 0 ppd round from layer 1, 1 ppd round after a match, 2 plain step
+  // captured rounds: 0 ppd round from layer 1, 1 ppd round after a match, 2 plain step, 3 ppd round after a
+  // match whose candidates were predicted by the round before
   int use_graphs;
   hipGraphExec_t graph[4];
-  int graph_chunks[4];   // attention grid (128-position chunks) each graph was captured with
+  int graph_chunks[4];   // attention grid (64-position chunks) each graph was captured with
   int gmax1, gmax2, gmaxd; // workgroup budget of a GEMM launch: one group / per group of a two-group launch / per chain of the parallel phase
   int in_dual;           // launches belong to one of two concurrent chains
   int skew;              // the candidates' chain starts half a layer after the main token's
