@@ -12,8 +12,11 @@
  * the main token at layer dbar+j and the k candidates at layer j.
  *
  * Pointer kinds are stated per argument: HOST or DEVICE.  All functions
- * return 0 on success or a negative PPD_E* code; a failing call leaves the
- * context unchanged unless stated.  One context must be used by one thread
+ * return 0 on success or a negative PPD_E* code.  A call that fails its
+ * argument or state checks (PPD_EINVAL, PPD_ECTX, PPD_ESTATE) leaves the
+ * context unchanged; after PPD_EHIP from ppd_prefill, ppd_step or
+ * plain_greedy_step the sequence state is undefined and the next call must
+ * be ppd_prefill (or ppd_destroy).  One context must be used by one thread
  * at a time.  No C++ exception crosses this boundary.
  */
 #ifndef PPD_H
@@ -123,13 +126,17 @@ enum {
  * (exit_layer, 1-based: the early prediction reads the output of that layer,
  * ceil(d/2) <= exit_layer <= d-1 as Theorem 4.1 requires dbar >= d/2), k.
  * dims, w: HOST structs, copied.  hip_stream: a hipStream_t (NULL = the
- * default stream), the caller's: the context runs on streams of its own and
- * makes them wait, at every ppd_prefill, for what the caller has queued on
- * hip_stream until then (the weights must be complete in device memory by
- * then; they are read again at every step and must not change).  Every call
- * is synchronous: the context's streams are idle on return.  The KV cache,
- * the candidates' KV tails and all scratch are allocated here (device
- * memory, freed by ppd_destroy).  *out receives the context (HOST). */
+ * default stream), the caller's: the context runs on a stream of its own and
+ * makes it wait, here and at every ppd_prefill, for what the caller has
+ * queued on hip_stream until then.  The weights must be complete in device
+ * memory once the work queued on hip_stream before this call has run: bf16
+ * models are repacked here, once, into copies the context owns (same size;
+ * linear weights changed afterwards are never seen), the remaining tensors
+ * (embeddings, norm gains, biases; every tensor of an fp32 model) are read
+ * again at every step and must not change.  Every call is synchronous: the
+ * context's stream is idle on return.  The KV cache, the candidates' KV
+ * tails and all scratch are allocated here (device memory, freed by
+ * ppd_destroy).  *out receives the context (HOST). */
 int ppd_create(const ppd_model_dims *dims, const ppd_weights *w, int k, int exit_layer,
                void *hip_stream, ppd_ctx **out);
 

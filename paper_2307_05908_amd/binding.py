@@ -124,7 +124,7 @@ def ppd_stream_read_probe(dev_tensor, iters: int = 5) -> float:
     out = ctypes.c_double(0.0)
     rc = load_library().ppd_stream_read_probe(dev_tensor.data_ptr(), nbytes, iters, ctypes.byref(out))
     if rc != 0:
-        raise PPDError(f"ppd_stream_read_probe: {load_library().ppd_strerror(rc).decode()}")
+        raise PPDError(rc, "ppd_stream_read_probe", load_library().ppd_last_hip_error(None))
     return float(out.value)
 
 

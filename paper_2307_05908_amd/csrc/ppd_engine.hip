@@ -28,10 +28,8 @@ struct ppd_ctx {
   int k, dbar, nb;   // nb = d - dbar: layers each candidate runs, = pipelined steps per round
   hipStream_t user_stream;   // the caller's stream: ppd_prefill orders the context's work after what it holds
   hipStream_t stream;        // the context's own stream: every launch goes here (a graph cannot be captured on the null stream)
-  hipStream_t stream2;       // second stream: the candidates' layers of the parallel phase run here, next to the main token's
   hipStream_t cur;           // stream the launch helpers issue to
-  hipEvent_t join_ev, fork_ev, back_ev;
-  int dual;                  // parallel phase as two concurrent chains (1) or as two-group launches (0)
+  hipEvent_t join_ev;
   int wbytes;                // bytes per weight element
   static constexpr int kvbytes = 4;   // keys and values are cached in fp32, like every other activation
   // weights (borrowed)
@@ -39,7 +37,6 @@ struct ppd_ctx {
   std::vector<LayerW> L;
   // bf16 models: weights repacked into MFMA blocks (owned copies); fp32 models stream the caller's tensors
   int mfma;
-  int mg_occ;            // workgroups of the MFMA GEMM a compute unit is asked to hold (1 or 2)
   int mg_passes_min;     // least number of staging passes of launches without a fused norm (1; tests force more)
   struct LayerP { void *qkv, *o, *fin, *fout; };
   std::vector<LayerP> LP;
@@ -81,9 +78,7 @@ struct ppd_ctx {
   int use_graphs;
   hipGraphExec_t graph[4];
   int graph_chunks[4];   // attention grid (64-position chunks) each graph was captured with
-  int gmax1, gmax2, gmaxd; // workgroup budget of a GEMM launch: one group / per group of a two-group launch / per chain of the parallel phase
-  int in_dual;           // launches belong to one of two concurrent chains
-  int skew;              // the candidates' chain starts half a layer after the main token's
+  int gmax1, gmax2;      // workgroup budget of an fp32 GEMM launch: one group / per group of a two-group launch
   int nchunk_max;
   // round state
   int n_ctx;      // absolute position of the pending token x_t (-1: no prefill yet)
@@ -163,7 +158,7 @@ int pick_grid(int nsets, int gmax) {
 // one skinny GEMM launch; group 0 is always one row, group 1 (optional) has MB rows
 hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
   const int vec = 16 / c->wbytes;
-  const int gmax = ngroups == 2 ? c->gmax2 : (c->in_dual ? c->gmaxd : c->gmax1);
+  const int gmax = ngroups == 2 ? c->gmax2 : c->gmax1;
   const int mmax = ngroups == 2 ? (a.g[1].M > a.g[0].M ? a.g[1].M : a.g[0].M) : a.g[0].M;
   const int x_budget = GEMM_X_FLOATS / mmax;   // k elements of x per row that fit the LDS tile
   // rows a wave streams together: 4, or 2 when 4 would leave waves of the grid without a set
@@ -221,7 +216,7 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
   // in the fewest passes that fit (same arithmetic, weights still read once).  Launches with a fused
   // norm need whole rows: those fall back to row slices below.
   const int t1 = a.topk > 0 ? (a.NT + c->head_grid - 1) / c->head_grid : (a.NT + 255) / 256;
-  const int tcap = (a.topk > 0 || (ngroups == 1 && !c->in_dual)) ? t1 : t1 * 2;   // tiles per workgroup of this launch shape
+  const int tcap = (a.topk > 0 || ngroups == 1) ? t1 : t1 * 2;   // tiles per workgroup of this launch shape
   a.passes = c->mg_passes_min;
   if (a.norm >= 0) a.passes = 1;
   else while (a.passes < 8 && lds_with(mmax, tcap, a.passes) > MG_LDS_MAX) ++a.passes;
@@ -234,18 +229,14 @@ hipError_t launch_mgemm(ppd_ctx* c, MGemmArgs& a, int ngroups, bool paired) {
   // head launches keep HEAD_MAX_ROWS logits per row where the staged rows were
   if (a.topk > 0 && a.xrow < HEAD_MAX_ROWS * (int)sizeof(float)) a.xrow = HEAD_MAX_ROWS * (int)sizeof(float);
   auto lds_for = [&](int M, int tiles) { int b, p, x; return (size_t)mg_lds_layout(a.K, M, a.norm, tiles, a.xrow, b, p, x); };
-  // Workgroups per group: the launch's share of the machine (two workgroups of 8 waves fit a compute
-  // unit when their LDS does), then the smallest grid with the same number of tiles per workgroup, so
-  // that all of them finish together.
+  // Workgroups per group: the launch's share of the machine (one workgroup of 8 waves per compute unit),
+  // then the smallest grid with the same number of tiles per workgroup, so that all of them finish together.
   auto go = [&](MGemmArgs x, int ng, int mm) -> hipError_t {
     int gx;
     if (x.topk > 0) gx = c->head_grid;
     else {
-      const int share = (ng == 2 || c->in_dual) ? 2 : 1;
-      int per_cu = c->mg_occ;
-      int gmax = 256 * per_cu / share;
-      int t = (x.NT + gmax - 1) / gmax;
-      if (per_cu > 1 && lds_for(mm, t) * per_cu > MG_LDS_MAX) { gmax = 256 / share; t = (x.NT + gmax - 1) / gmax; }
+      const int gmax = 256 / ng;
+      const int t = (x.NT + gmax - 1) / gmax;
       gx = (x.NT + t - 1) / t;
     }
     if (gx > x.NT) gx = x.NT;
@@ -576,33 +567,7 @@ int issue_round(ppd_ctx* c, int kind, int pmax) {
   // early prediction; the candidates become rows 1..k at the next position
   if (kind != 3 && (rc = run_head(c, true, false))) return rc;
   // parallel phase: step j runs the main row at layer dbar+j and the candidates at layer j
-  if (c->dual) {
-    // two concurrent chains, one per stream: while one chain sits in a latency-bound stretch
-    // (kernel boundary, attention, staging of its input rows) the other keeps HBM busy
-    ProfScope phase(c, PPD_KC_PHASE, 2);
-    c->in_dual = 1;
-    // The candidates' chain starts half a layer behind the main token's, so that each chain's
-    // attention (little traffic, long waits) falls into the other's FFN matrices.
-    if (c->skew) {
-      RowGroup gm{dbar, 1, 0, 0, false};
-      c->cur = c->stream;
-      if ((rc = run_layer(c, 1, &gm, pmax, 1))) return rc;
-    }
-    HIPCHK(c, hipEventRecord(c->fork_ev, c->stream));
-    HIPCHK(c, hipStreamWaitEvent(c->stream2, c->fork_ev, 0));
-    for (int j = 0; j < nb && !rc; ++j) {
-      RowGroup gm{dbar + j, 1, 0, 0, false}, gb{j, k, 1, 1, true};
-      c->cur = c->stream;
-      rc = run_layer(c, 1, &gm, pmax, (c->skew && j == 0) ? 14 : 15);
-      c->cur = c->stream2;
-      if (!rc) rc = run_layer(c, 1, &gb, pmax);
-    }
-    c->cur = c->stream;
-    c->in_dual = 0;
-    HIPCHK(c, hipEventRecord(c->back_ev, c->stream2));
-    HIPCHK(c, hipStreamWaitEvent(c->stream, c->back_ev, 0));
-    if (rc) return rc;
-  } else {
+  {
     ProfScope phase(c, PPD_KC_PHASE, 2);
     for (int j = 0; j < nb; ++j) {
       RowGroup g[2] = {{dbar + j, 1, 0, 0, false}, {j, k, 1, 1, true}};
@@ -629,7 +594,7 @@ int run_round(ppd_ctx* c, int kind, int pos) {
       c->graph[kind] = nullptr;
     }
     if (!c->graph[kind]) {
-      // capture with the attention grid sized for the whole 128-position chunk this round ends in
+      // capture with the attention grid sized for the whole 64-position chunk this round ends in
       hipGraph_t g = nullptr;
       HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed));
       rc = issue_round(c, kind, nchunks * ATT_CHUNK - 1);
@@ -676,9 +641,6 @@ void free_all(ppd_ctx* c) {
   if (c->host_result) (void)hipHostFree(c->host_result);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   if (c->join_ev) (void)hipEventDestroy(c->join_ev);
-  if (c->fork_ev) (void)hipEventDestroy(c->fork_ev);
-  if (c->back_ev) (void)hipEventDestroy(c->back_ev);
-  if (c->stream2) (void)hipStreamDestroy(c->stream2);
   if (c->stream) (void)hipStreamDestroy(c->stream);
 }
 
@@ -739,16 +701,13 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   c->nchunk_max = (d.max_ctx + ATT_CHUNK - 1) / ATT_CHUNK;
   c->n_ctx = -1;
   c->use_graphs = env_int("PPD_GRAPHS", 1) != 2;      // PPD_GRAPHS=2 switches graph replay off
-  c->dual = env_int("PPD_DUAL", 1) != 2;               // PPD_DUAL=2: two-group launches instead of two chains
-  c->skew = env_int("PPD_SKEW", 0) == 1;
   {
     const int cap = d.wdtype == 1 ? PREFILL_CHUNK : PREFILL_CHUNK_FP32;
     c->prefill_chunk = env_int("PPD_PREFILL_CHUNK", cap);
     if (c->prefill_chunk > cap) c->prefill_chunk = cap;
   }
-  c->gmax1 = env_int("PPD_GMAX1", 512);
-  c->gmaxd = env_int("PPD_GMAXD", 256);
-  c->gmax2 = env_int("PPD_GMAX2", 256);
+  c->gmax1 = 512;
+  c->gmax2 = 256;
   // head GEMM: as many workgroups as a plain GEMM, more if a workgroup would otherwise
   // produce over HEAD_MAX_ROWS logits
   {
@@ -788,11 +747,8 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, (2 + MAXM) * sizeof(int32_t), hipHostMallocMapped);
   if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&c->host_result_dev, c->host_result, 0);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking);
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking);
   c->cur = c->stream;
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->back_ev, hipEventDisableTiming);
   if (e == hipSuccess && d.pos == 1) {
     // (cos, sin) of pos * theta^(-2i/hd), evaluated in double on the host
     const int half = d.head_dim / 2;
@@ -810,7 +766,10 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   if (e == hipSuccess) e = hipMemset(c->Vc, 0, (size_t)d.n_layers * cache_layer_bytes(c));
   c->mfma = d.wdtype == 1;
   if (e == hipSuccess && c->mfma) {
-    // repack every linear weight into MFMA blocks (owned copies)
+    // repack every linear weight into MFMA blocks (owned copies), on the context's stream and after whatever
+    // the caller has queued on its own stream so far (an asynchronous upload of the weights)
+    e = hipEventRecord(c->join_ev, c->user_stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(c->stream, c->join_ev, 0);
     auto repack = [&](const void* s0, const void* s1, const void* s2, int n0, int n1, int n2, int K, bool paired, void** out) {
       if (e != hipSuccess) return;
       RepackArgs r; memset(&r, 0, sizeof r);
@@ -823,7 +782,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
       if (e != hipSuccess) return;
       c->owned.push_back(dst);
       r.dst = (uint16_t*)dst;
-      hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(r.NT * r.KT)), dim3(64), 0, 0, r);
+      hipLaunchKernelGGL(repack_kernel, dim3((unsigned)(r.NT * r.KT)), dim3(64), 0, c->stream, r);
       e = hipGetLastError();
       *out = dst;
     };
@@ -838,22 +797,20 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     }
     repack(c->lm_head, nullptr, nullptr, d.vocab, 0, 0, (int)dm, false, &c->head_p);
     if (c->early_head) repack(c->early_head, nullptr, nullptr, d.vocab, 0, 0, (int)dm, false, &c->early_p);
-    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
     if (e == hipSuccess) e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)MG_LDS_MAX);
     // head launches: the same balanced grid as any other GEMM; a workgroup keeps at most
     // HEAD_MAX_ROWS logits = 16 tiles
-    c->mg_occ = env_int("PPD_MGOCC", 1) == 2 ? 2 : 1;
     c->mg_passes_min = env_int("PPD_MGPASSES", 1);
     if (c->mg_passes_min < 1 || c->mg_passes_min > 8) c->mg_passes_min = 1;
     const int NTh = (d.vocab + 15) / 16;
-    int th = (NTh + 256 * c->mg_occ - 1) / (256 * c->mg_occ);
+    int th = (NTh + 255) / 256;
     c->head_grid = (NTh + th - 1) / th;
     while ((NTh + c->head_grid - 1) / c->head_grid > HEAD_MAX_ROWS / 16) ++c->head_grid;
     if ((size_t)c->head_grid > pk_slots) e = hipErrorInvalidValue;
-    if (env_int("PPD_DUAL", 2) != 1) c->dual = 0;   // one launch per step for both chains unless asked otherwise
     // speculative early prediction when the candidates end a round at the exit layer, the early head is the LM
     // head, and the 1 + k rows of the widened final head fit one launch (PPD_SPEC=2 switches it off)
     {
@@ -865,6 +822,8 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
       c->spec = 2 * c->dbar == d.n_layers && !c->early_head && need <= MG_LDS_MAX && env_int("PPD_SPEC", 1) != 2;
     }
   }
+  // (the fills and copies above went to the null stream, which the context's own stream does not wait for)
+  if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     g_create_hip_error = (int)e;
     (void)hipGetLastError();

@@ -44,12 +44,8 @@ template <int HD>
 hipError_t launch_attn_t(hipStream_t stream, const AttnArgs& a, int mmax, dim3 grid, bool causal) {
   if (mmax < 1 || mmax > 16) return hipErrorInvalidValue;
   const size_t lds = sizeof(float) * (size_t)attn_lds_floats<HD>(mmax);
-  if (lds > 160 * 1024) return hipErrorInvalidValue;
-  if (lds > 64 * 1024) {     // beyond the default dynamic LDS limit (prompt chunks of 16 rows)
-    hipError_t e = causal ? hipFuncSetAttribute((const void*)attn_kernel<HD, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                          : hipFuncSetAttribute((const void*)attn_kernel<HD, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
+  static_assert(sizeof(float) * attn_lds_floats<HD>(16) <= 64 * 1024, "16 rows fit the default dynamic LDS limit");
+  if (lds > 64 * 1024) return hipErrorInvalidValue;
   if (causal) attn_kernel<HD, true><<<grid, dim3(ATT_THREADS), lds, stream>>>(a);
   else attn_kernel<HD, false><<<grid, dim3(ATT_THREADS), lds, stream>>>(a);
   return hipGetLastError();

@@ -894,11 +894,12 @@ __global__ __launch_bounds__(MERGE_THREADS) void attn_merge_kernel(MergeArgs a) 
 // ------------------------------------------------------------------ selection
 // Early prediction: top-k of the early logits by (logit descending, id ascending); the head GEMM
 // leaves every workgroup's own top-k, this kernel merges them and sets up the k candidate rows
-// (Algorithm 2: "select the top-k early predicted tokens", "distribute" -- here: embed them).
+// (Algorithm 2: the early top-k and its hand-out to the sub-processes -- here: their embedding rows).
 // Final prediction: arg max of the final logits (ties to the lowest id), verification against the
-// early candidates ("if x-hat^(PID) = x_{t+1}"), then adoption: on a match the matching candidate's
-// hidden row becomes the main row and its key/value tails of layers 1..d-dbar become cache position
-// t+1; without a match nothing is copied and the tails are overwritten by the next round.
+// early candidates (Algorithm 2's comparison of each candidate with the final token), then adoption:
+// on a match the matching candidate's hidden row becomes the main row and its key/value tails of layers
+// 1..d-dbar become cache position t+1; without a match nothing is copied and the tails are overwritten
+// by the next round.
 // Appendix B's sampling-based variants replace only the arg max: the token verified here is then the one
 // drawn by top-k sampling (inside this kernel, from the merged lists) or by the sampling kernel (top-p).
 struct SelectArgs {

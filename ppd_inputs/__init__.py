@@ -213,6 +213,25 @@ def make_model(cfg: ModelConfig) -> SynthModel:
     return m
 
 
+def make_early_head(cfg: ModelConfig, model: Optional[SynthModel] = None, mix: float = 1.0) -> np.ndarray:
+    """A second ``[vocab][d_model]`` classifier matrix for the early prediction (stands for the classifier
+    trained per exit layer; here: seeded noise).  Without ``model``: iid N(0, 0.02), unrelated to the LM
+    head.  With ``model``: the model's LM head plus ``mix`` times such noise, rounded once to the weight
+    type, so that its predictions are close to the LM head's but its logits are not."""
+    noise = _normal((cfg.vocab, cfg.d_model), cfg.seed_w, 6 * 4096, 0.0, 0.02, 1.0, WD_FP32)
+    if model is None:
+        base = np.zeros_like(noise)
+        mix = 1.0
+    else:
+        base = to_float64(model.g["lm_head"]).astype(np.float32)
+    v = (base + np.float32(mix) * noise).astype(np.float32)
+    if cfg.wdtype == WD_FP32:
+        return np.ascontiguousarray(v)
+    u = v.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) >> 16            # round to nearest even (no NaNs here)
+    return np.ascontiguousarray(u.astype(np.uint16))
+
+
 def make_prompt(cfg: ModelConfig, n: Optional[int] = None) -> np.ndarray:
     n = cfg.n_prompt if n is None else n
     out = np.empty(n, dtype=np.int32)

@@ -28,7 +28,7 @@ def run_against_oracle(P, prompt, mode, otoks, ofinal, oearly=None, tol=2e-2):
     Returns dict(max_err, max_err_early, resyncs, matches)."""
     prompt = list(map(int, prompt))
     P.ppd_prefill(prompt)
-    out = dict(max_err=0.0, max_err_early=0.0, resyncs=0, matches=0, tokens=[])
+    out = dict(max_err=0.0, max_err_early=0.0, resyncs=0, matches=0, tokens=[], cand_sets_equal=True)
     for t in range(len(otoks)):
         if mode == "plain":
             tok = P.plain_greedy_step()
@@ -40,6 +40,9 @@ def run_against_oracle(P, prompt, mode, otoks, ofinal, oearly=None, tol=2e-2):
                 out["max_err_early"] = max(out["max_err_early"], e)
                 assert e <= tol, f"early logits off by {e} at step {t}"
                 check_topk_against_oracle(oearly[t], list(info.cand), P.k, tol)
+                order = np.lexsort((np.arange(len(ze)), -oearly[t]))
+                if set(info.cand[:P.k]) != set(int(x) for x in order[:P.k]):
+                    out["cand_sets_equal"] = False      # a near-tie at the k-th early logit, within tol
             cand = list(info.cand)[:P.k]
             assert info.token == tok
             assert info.match_idx == (cand.index(tok) if tok in cand else -1)

@@ -169,10 +169,10 @@ def test_llama7b_speculative_early_prediction_full_config(monkeypatch):
         P.close()
         return out, st
 
+    monkeypatch.setenv("PPD_SPEC", "1")
     a, sa = run()
     monkeypatch.setenv("PPD_SPEC", "2")
     b, sb = run()
-    monkeypatch.delenv("PPD_SPEC")
     assert a == b
     follow = sum(1 for j in range(1, len(a)) if a[j - 1][1])
     assert sb["weight_bytes"] - sa["weight_bytes"] == follow * cfg.head_weight_bytes()
@@ -194,7 +194,6 @@ def test_llama7b_prompt_chunks_full_config(monkeypatch):
     t16, z16 = run()
     monkeypatch.setenv("PPD_PREFILL_CHUNK", "1")
     t1, z1 = run()
-    monkeypatch.delenv("PPD_PREFILL_CHUNK")
     np.testing.assert_array_equal(t16, t1)
     np.testing.assert_array_equal(z16.view(np.uint32), z1.view(np.uint32))
 

@@ -15,7 +15,7 @@ SMALL = {
     "tiny": small_cfg("tiny"),
     "opt": small_cfg("opt"),
     "llama": small_cfg("llama"),
-    # several attention chunks (128 positions each) and a ragged last one
+    # several attention chunks (64 positions each) and a ragged last one
     "llama_long": small_cfg("llama", max_ctx=420, n_prompt=300, n_gen=24),
     "opt_long": small_cfg("opt", max_ctx=300, n_prompt=250, n_gen=16),
 }
@@ -49,8 +49,10 @@ def test_ppd_matches_oracle(setup, k):
         r = run_against_oracle(P, prompt, "ppd", ro["tokens"], ro["final_logits"], ro["early_logits"], tol=TOL[cfg.wdtype])
         print(cfg.name, "k", k, "dbar", dbar, "max|dlogit|", r["max_err"], r["max_err_early"], "resyncs", r["resyncs"],
               "matches", r["matches"], "oracle matches", ro["stats"]["matches"])
-        if r["resyncs"] == 0:
-            assert r["matches"] == ro["stats"]["matches"] or True   # candidates may legally differ at ties
+        # (per round, run_against_oracle has checked the match index against the GPU's own candidates and the
+        # candidates against the oracle's early logits; the totals agree whenever no candidate set differed)
+        if r["resyncs"] == 0 and r["cand_sets_equal"]:
+            assert r["matches"] == ro["stats"]["matches"]
         P.close()
 
 
@@ -222,7 +224,6 @@ def test_staging_in_passes_is_bit_identical(family, monkeypatch):
         t, z = run()
         assert t == ref_t
         np.testing.assert_array_equal(z.view(np.uint32), ref_z.view(np.uint32))
-    monkeypatch.delenv("PPD_MGPASSES")
 
 
 @pytest.mark.gpu
@@ -255,10 +256,10 @@ def test_speculative_early_prediction_changes_nothing_but_the_traffic(family, k,
         P.close()
         return toks, np.stack(zs), np.stack(es), infos, st
 
+    monkeypatch.setenv("PPD_SPEC", "1")
     t1, z1, e1, i1, st1 = run()
     monkeypatch.setenv("PPD_SPEC", "2")
     t0, z0, e0, i0, st0 = run()
-    monkeypatch.delenv("PPD_SPEC")
     assert t1 == t0 and i1 == i0
     np.testing.assert_array_equal(z1.view(np.uint32), z0.view(np.uint32))
     np.testing.assert_array_equal(e1.view(np.uint32), e0.view(np.uint32))
@@ -300,4 +301,49 @@ def test_prompt_in_chunks_is_token_by_token_bit_exact(name, monkeypatch):
         for a, b in list(zip(got[n], ref)) + list(zip(got16[n], ref)):
             np.testing.assert_array_equal(np.asarray(a).view(np.uint32) if np.asarray(a).dtype == np.float32 else a,
                                           np.asarray(b).view(np.uint32) if np.asarray(b).dtype == np.float32 else b)
-    monkeypatch.delenv("PPD_PREFILL_CHUNK")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("family", ["tiny", "opt", "llama"])
+@pytest.mark.parametrize("near", [False, True])
+def test_separate_early_head_matches_oracle_and_keeps_the_output(family, near):
+    """Sec. 4.3: a classifier of its own for the exit layer (`early_head`).  The early logits follow the oracle
+    run with the same matrix, the candidates are their top-k, tokens and final logits stay those of plain greedy
+    decoding on the GPU bit for bit.  near = False: an unrelated random matrix (no round matches); near = True:
+    the LM head plus noise on a model with damped late blocks, so that most rounds match and the rounds after a
+    match start mid-stack and run their own early head (no speculative prediction with a separate classifier).
+    Exit layers d/2 and d-1."""
+    cfg = small_cfg(family, alpha=0.05) if near else small_cfg(family)
+    m = pi.make_model(cfg)
+    E = pi.make_early_head(cfg, m, mix=0.3) if near else pi.make_early_head(cfg)
+    dev = binding.upload_model(m)
+    import torch
+    Et = torch.from_numpy(E.view(np.int16) if E.dtype == np.uint16 else E).to("cuda:0")
+    if E.dtype == np.uint16:
+        Et = Et.view(torch.bfloat16)
+    o = oracle.Oracle(m, early_head=E)
+    prompt = pi.make_prompt(cfg)
+    d, ell, k = cfg.n_layers, cfg.n_gen, 3
+    P0 = binding.PPD(cfg, dev)
+    ptoks, pz, _ = gpu_generate(P0, prompt, ell, "plain")
+    P0.close()
+    for dbar in sorted({(d + 1) // 2, d - 1}):
+        ro = o.ppd(prompt, ell, k, dbar, want_logits=True)
+        P = binding.PPD(cfg, dev, k=k, exit_layer=dbar, early_head=Et)
+        r = run_against_oracle(P, prompt, "ppd", ro["tokens"], ro["final_logits"], ro["early_logits"], tol=TOL[cfg.wdtype])
+        print(cfg.name, "early_head near", near, "dbar", dbar, "max|dlogit|", r["max_err"], r["max_err_early"],
+              "matches", r["matches"], "oracle", ro["stats"]["matches"], flush=True)
+        if near:
+            assert r["matches"] > ell // 4
+        elif r["resyncs"] == 0 and r["cand_sets_equal"]:
+            assert r["matches"] == ro["stats"]["matches"]
+        toks, z, infos = gpu_generate(P, prompt, ell, "ppd")
+        np.testing.assert_array_equal(toks, ptoks)
+        np.testing.assert_array_equal(z.view(np.uint32), pz.view(np.uint32))
+        # the default context (LM head as the early classifier) predicts something else
+        Pd = binding.PPD(cfg, dev, k=k, exit_layer=dbar)
+        Pd.ppd_prefill(prompt); P.ppd_prefill(prompt)
+        Pd.ppd_step(); P.ppd_step()
+        assert np.abs(Pd.ppd_get_early_logits() - P.ppd_get_early_logits()).max() > 1e-2
+        Pd.close()
+        P.close()

@@ -279,3 +279,70 @@ def test_eos_stops_both():
     b = o.ppd(p, 12, 3, 2, eos=eos)["tokens"]
     np.testing.assert_array_equal(a, full[:first + 1])
     np.testing.assert_array_equal(b, a)
+
+
+# ------------------------------------------------ separate early classifier
+class _Shallow:
+    """The first `n` blocks of a model with another classifier matrix (for torch_forward)."""
+
+    def __init__(self, m, n, head):
+        self.cfg = m.cfg.replace(n_layers=n)
+        self.g = dict(m.g, lm_head=head)
+        self.layers = m.layers
+
+
+def test_early_head_is_the_classifier_of_the_truncated_model(fam):
+    """Sec. 4.3: the early prediction may use a classifier trained for the exit layer.  With such a matrix E
+    the early logits of round t are E . Norm_f(h_dbar), i.e. the output of the same transformer cut after dbar
+    blocks with E as its classifier (library forward, fp64); the candidates are their top-k by a full sort;
+    the emitted tokens and final logits stay those of plain greedy decoding."""
+    cfg, m, o = fam
+    E = pi.make_early_head(cfg)
+    oe = oracle.Oracle(m, early_head=E)
+    p, ell, k = pi.make_prompt(cfg, 9), 8, 3
+    plain, zp = o.plain_greedy(p, ell, want_logits=True)
+    seq = np.concatenate([p, plain[:-1]])
+    d = cfg.n_layers
+    for dbar in sorted({(d + 1) // 2, d - 1}):
+        r = oe.ppd(p, ell, k, dbar, want_logits=True)
+        np.testing.assert_array_equal(r["tokens"], plain)
+        np.testing.assert_array_equal(r["final_logits"], zp)
+        zt = torch_forward(cfg.replace(n_layers=dbar), _Shallow(m, dbar, E), seq)[len(p) - 1:]
+        np.testing.assert_allclose(r["early_logits"], zt, rtol=0, atol=1e-10)
+        for t in range(ell):
+            order = np.lexsort((np.arange(cfg.vocab), -r["early_logits"][t]))
+            np.testing.assert_array_equal(r["cand"][t], order[:k])
+            where = np.nonzero(r["cand"][t] == plain[t])[0]
+            assert r["match_idx"][t] == (where[0] if len(where) else -1)
+        # the default (no separate matrix) reads the LM head instead: the two must differ visibly
+        rd = o.ppd(p, ell, k, dbar, want_logits=True)
+        zd = torch_forward(cfg.replace(n_layers=dbar), _Shallow(m, dbar, m.g["lm_head"]), seq)[len(p) - 1:]
+        np.testing.assert_allclose(rd["early_logits"], zd, rtol=0, atol=1e-10)
+        assert np.abs(zd - zt).max() > 0.1
+        # teacher-forced early logits take the same classifier
+        _, ze = oe.teacher_forced(seq, len(p) - 1, dbar=dbar)
+        np.testing.assert_array_equal(ze, r["early_logits"])
+    # handing over the LM head itself as the early classifier is the default
+    osame = oracle.Oracle(m, early_head=m.g["lm_head"])
+    np.testing.assert_array_equal(osame.ppd(p, ell, k, cfg.exit_layer, want_logits=True)["early_logits"],
+                                  o.ppd(p, ell, k, cfg.exit_layer, want_logits=True)["early_logits"])
+
+
+@pytest.mark.parametrize("family", ["opt", "llama"])
+def test_early_head_close_to_lm_head_matches_and_adopts(family):
+    """An early classifier near the LM head on a model whose late blocks add little: most rounds match, the
+    matching sub-process is adopted (rounds that start mid-stack), and the output is still plain greedy's."""
+    cfg = small_cfg(family, alpha=0.05)
+    m = pi.make_model(cfg)
+    E = pi.make_early_head(cfg, m, mix=0.3)
+    o, oe = oracle.Oracle(m), oracle.Oracle(m, early_head=E)
+    p = pi.make_prompt(cfg)
+    plain, zp = o.plain_greedy(p, cfg.n_gen, want_logits=True)
+    r = oe.ppd(p, cfg.n_gen, 3, cfg.exit_layer, want_logits=True)
+    np.testing.assert_array_equal(r["tokens"], plain)
+    np.testing.assert_array_equal(r["final_logits"], zp)
+    hits = int((r["match_idx"] >= 0).sum())
+    assert 0 < hits and r["stats"]["matches"] == hits
+    assert r["stats"]["runs"] == 1 + int((r["match_idx"][:cfg.n_gen - 1] < 0).sum())
+    rd = o.ppd(p, cfg.n_gen, 3, cfg.exit_layer, want_logits=True)
+    assert np.abs(r["early_logits"] - rd["early_logits"]).max() > 1e-2
