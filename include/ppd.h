@@ -34,6 +34,7 @@ extern "C" {
 #define PPD_ECTX (-3)   /* context window exhausted */
 #define PPD_ESTATE (-4) /* call out of order (e.g. step before prefill) */
 #define PPD_EHIP (-5)   /* a HIP call failed; ppd_last_hip_error() tells which */
+#define PPD_ELIMIT (-6) /* a size beyond the fixed maximum an entry point documents */
 
 #define PPD_MAX_K 8
 
@@ -225,6 +226,21 @@ int ppd_time_ffn_in(ppd_ctx *ctx, int reps, double *ms_per_launch);
  * output): the streaming rate this GPU reaches, next to which the decode kernels' rates are read.
  * bytes must be a positive multiple of 16; the buffer is only read.  Runs on its own stream, synchronous. */
 int ppd_stream_read_probe(const void *dev_buf, uint64_t bytes, int iters, double *gbps);
+
+/* The early prediction of Sec. 3 on its own, outside any context: logits = head . Norm(h) for one
+ * intermediate hidden row (the LM classifier applied to the exit layer's state; Sec. 4.3: the final layer's
+ * classifier, or one trained for that layer), and their top-k by (logit descending, id ascending) -- the
+ * k candidate tokens Algorithm 2 hands to the sub-processes.  For callers that run the layers themselves.
+ * All tensors DEVICE, borrowed for the call: h float[d_model] (16-byte aligned); norm_g, norm_b (norm_b only for
+ * norm == 0, LayerNorm) and head ([vocab][d_model] row-major, rows 16-byte aligned) of type wdtype (0 fp32,
+ * 1 bf16); d_model a multiple of 8; 1 <= k <= min(PPD_MAX_K, vocab).  Outputs, DEVICE: ids_out int32[k];
+ * vals_out float[k] (their logits) or NULL; logits_out float[vocab] or NULL.  Work is queued on hip_stream (a
+ * hipStream_t, NULL = the default stream).  This call allocates its scratch (the logits when logits_out is NULL,
+ * one top-k list per workgroup) with hipMalloc, waits for hip_stream and frees it: synchronous, outputs complete
+ * on return.  PPD_EINVAL for bad arguments, PPD_ENOMEM / PPD_EHIP (ppd_last_hip_error(NULL)) otherwise. */
+int ppd_early_topk(int d_model, int vocab, int norm, float norm_eps, int wdtype, const void *norm_g,
+                   const void *norm_b, const void *head, const float *h, int k, int32_t *ids_out,
+                   float *vals_out, float *logits_out, void *hip_stream);
 
 void ppd_destroy(ppd_ctx *ctx);
 

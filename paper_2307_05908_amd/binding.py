@@ -51,7 +51,7 @@ class Stats(ctypes.Structure):
 
 EXPORTS = ("ppd_create", "ppd_reset", "ppd_prefill", "ppd_step", "plain_greedy_step", "ppd_get_logits",
            "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_set_graphs", "ppd_set_sampling", "ppd_get_kernel_time",
-           "ppd_time_ffn_in", "ppd_stream_read_probe", "ppd_destroy",
+           "ppd_time_ffn_in", "ppd_stream_read_probe", "ppd_early_topk", "ppd_destroy",
            "ppd_strerror", "ppd_last_hip_error")
 
 _lib = None
@@ -84,6 +84,7 @@ def load_library() -> ctypes.CDLL:
     lib.ppd_get_kernel_time.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
     lib.ppd_time_ffn_in.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_stream_read_probe.argtypes = [vp, ctypes.c_uint64, ci, ctypes.POINTER(ctypes.c_double)]
+    lib.ppd_early_topk.argtypes = [ci, ci, ci, ctypes.c_float, ci, vp, vp, vp, vp, ci, vp, vp, vp, vp]
     lib.ppd_destroy.argtypes = [vp]
     lib.ppd_destroy.restype = None
     lib.ppd_strerror.argtypes = [ci]
@@ -126,6 +127,30 @@ def ppd_stream_read_probe(dev_tensor, iters: int = 5) -> float:
     if rc != 0:
         raise PPDError(rc, "ppd_stream_read_probe", load_library().ppd_last_hip_error(None))
     return float(out.value)
+
+
+def _early_topk_call(fn_name, h, norm_g, norm_b, head, k, norm, norm_eps, want_logits, stream):
+    import torch
+    lib = load_library()
+    vocab, d_model = head.shape
+    wdtype = 0 if head.dtype == torch.float32 else 1
+    ids = torch.empty(k, dtype=torch.int32, device=h.device)
+    vals = torch.empty(k, dtype=torch.float32, device=h.device)
+    logits = torch.empty(vocab, dtype=torch.float32, device=h.device) if want_logits else None
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = getattr(lib, fn_name)(d_model, vocab, int(norm), float(norm_eps), wdtype, norm_g.data_ptr(),
+                               None if norm_b is None else norm_b.data_ptr(), head.data_ptr(), h.data_ptr(), int(k),
+                               ids.data_ptr(), vals.data_ptr(), None if logits is None else logits.data_ptr(),
+                               ctypes.c_void_p(st.cuda_stream))
+    if rc != 0:
+        raise PPDError(rc, fn_name, lib.ppd_last_hip_error(None))
+    return ids, vals, logits
+
+
+def ppd_early_topk(h, norm_g, norm_b, head, k, norm, norm_eps=1e-5, want_logits=False, stream=None):
+    """Stand-alone early prediction on device tensors: (ids int32[k], logits of those float[k], all logits or None).
+    h: float32 [d_model]; norm_g / norm_b / head: float32 or bfloat16 tensors of the model's weight type."""
+    return _early_topk_call("ppd_early_topk", h, norm_g, norm_b, head, k, norm, norm_eps, want_logits, stream)
 
 
 class PPD:

@@ -98,7 +98,7 @@ struct ppd_ctx {
 
 namespace {
 
-int g_create_hip_error = 0;   // hipError_t of the last ppd_create that failed with PPD_EHIP / PPD_ENOMEM
+int g_create_hip_error = 0;   // hipError_t of the last context-free call (ppd_create included) that failed with PPD_EHIP / PPD_ENOMEM
 
 #define HIPCHK(ctx, call)                       \
   do {                                          \
@@ -140,21 +140,6 @@ void prof_collect(ppd_ctx* c) {   // stream must be idle
 }
 
 // ------------------------------------------------------------ launch helpers
-// Workgroups per group for a GEMM with `nsets` row sets: each workgroup has four waves and every
-// wave takes ceil(nsets / waves) sets, so pick the count in [gmax/2, gmax] that wastes the fewest
-// wave slots (ties: the larger grid).
-int pick_grid(int nsets, int gmax) {
-  int need = (nsets + GEMM_WAVES - 1) / GEMM_WAVES;
-  if (need <= gmax) return need < 1 ? 1 : need;
-  int best = gmax; double best_eff = 0.0;
-  for (int g = gmax; g >= gmax / 2 && g >= 1; --g) {
-    int nw = g * GEMM_WAVES, nit = (nsets + nw - 1) / nw;
-    double eff = (double)nsets / ((double)nit * nw);
-    if (eff > best_eff + 1e-9) { best_eff = eff; best = g; }
-  }
-  return best;
-}
-
 // one skinny GEMM launch; group 0 is always one row, group 1 (optional) has MB rows
 hipError_t launch_gemm(ppd_ctx* c, GemmArgs& a, int ngroups, bool paired) {
   const int vec = 16 / c->wbytes;
@@ -653,6 +638,10 @@ int env_int(const char* name, int dflt) {
 
 }  // namespace
 
+namespace ppd {
+void set_global_hip_error(int e) { g_create_hip_error = e; }
+}  // namespace ppd
+
 extern "C" {
 
 int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit_layer, void* hip_stream,
@@ -711,11 +700,7 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   // head GEMM: as many workgroups as a plain GEMM, more if a workgroup would otherwise
   // produce over HEAD_MAX_ROWS logits
   {
-    const int nsets = (d.vocab + 3) / 4;                          // the head always streams four rows per wave
-    int g = pick_grid(nsets, c->gmax1);
-    const int sets_per_wg_cap = HEAD_MAX_ROWS / 4;               // per workgroup, all four waves together
-    while (((nsets + g * GEMM_WAVES - 1) / (g * GEMM_WAVES)) * GEMM_WAVES > sets_per_wg_cap) ++g;
-    c->head_grid = g;
+    c->head_grid = head_grid_valu(d.vocab, c->gmax1);
   }
   const size_t dm = d.d_model, R = 1 + k;
   const size_t RB = R > PREFILL_CHUNK ? R : PREFILL_CHUNK;   // activation rows: a round's 1 + k, or a prompt chunk
@@ -1081,6 +1066,7 @@ const char* ppd_strerror(int code) {
     case PPD_ECTX: return "context window exhausted";
     case PPD_ESTATE: return "call out of order";
     case PPD_EHIP: return "HIP call failed";
+    case PPD_ELIMIT: return "size beyond the fixed maximum of this entry point";
     default: return "unknown error";
   }
 }

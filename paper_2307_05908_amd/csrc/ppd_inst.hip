@@ -3,7 +3,7 @@
 
 namespace ppd {
 
-#if PPD_INST < 4
+#if PPD_INST < 4 || PPD_INST == 6
 // MA rows in group 0; MB rows in group 1 (0: single-group launch).  Launch shapes in use:
 // (1, 0) main token alone, (k, 0) the candidates alone, (1, k) both in one launch.
 template <typename WT, bool PAIRED, int WR>
@@ -28,7 +28,7 @@ hipError_t launch_gemm_t(hipStream_t stream, const GemmArgs& a, int MA, int MB, 
 }
 
 
-// (fp32 weights only: bf16 models run every GEMM on the MFMA kernel)
+// (fp32 weights, and one instance for row-major bf16: inside a context bf16 models run every GEMM on the MFMA kernel)
 #if PPD_INST == 0
 template hipError_t launch_gemm_t<float, false, 4>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
 #elif PPD_INST == 1
@@ -37,6 +37,9 @@ template hipError_t launch_gemm_t<float, true, 4>(hipStream_t, const GemmArgs&, 
 template hipError_t launch_gemm_t<float, false, 2>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
 #elif PPD_INST == 3
 template hipError_t launch_gemm_t<float, true, 2>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
+#elif PPD_INST == 6
+// bf16 weights as the caller holds them (row-major, not repacked): the stand-alone early prediction
+template hipError_t launch_gemm_t<bf16_t, false, 4>(hipStream_t, const GemmArgs&, int, int, dim3, size_t);
 #endif
 #else
 // mmax: the largest row count of the launch's groups (sizes LDS); causal: the prompt-chunk instance

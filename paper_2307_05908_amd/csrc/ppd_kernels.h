@@ -1206,26 +1206,19 @@ __global__ __launch_bounds__(SAMP_THREADS) void sample_kernel(SampleArgs a) {
 
 constexpr int SEL_THREADS = 256;
 
-// every workgroup merges the block candidates redundantly (they are few); winners land in win[]
-template <typename WT>
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
-  __shared__ float wv[SEL_THREADS / WAVE];
-  __shared__ int wi[SEL_THREADS / WAVE];
-  __shared__ int win[MAXM];
-  __shared__ float winv[MAXM];
-  __shared__ int s_midx, s_tok;
+// Merge of the head GEMM's block lists (nblk lists, the first kk entries of each valid, MAXM apart): the best nk
+// by (value descending, id ascending) land in win[] / winv[] (shared memory, MAXM entries each; wv / wi: shared
+// scratch of one entry per wave).  Called by all SEL_THREADS threads of a workgroup; ends with a barrier.
+__device__ __forceinline__ void merge_block_lists(const float* pkv, const int32_t* pki, int nblk, int kk, int nk,
+                                                  float* wv, int* wi, int* win, float* winv) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // merge of one row's block lists: the best nk by (value descending, id ascending) land in win[]
-  auto merge_row = [&](int prow, int nk) {
-  const float* pkv = a.pk_val + (size_t)prow * a.pk_stride * MAXM;
-  const int32_t* pki = a.pk_idx + (size_t)prow * a.pk_stride * MAXM;
-  const int total = a.nblk * a.kk;
-  // each thread scans its strided share and keeps its own sorted best nk
+  const int total = nblk * kk;
+  // each thread scans its strided share and keeps its own sorted best MAXM
   float lv[MAXM]; int li[MAXM];
 #pragma unroll
   for (int q = 0; q < MAXM; ++q) { lv[q] = -INFINITY; li[q] = 0x7fffffff; }
   for (int e = tid; e < total; e += SEL_THREADS) {
-    int b = e / a.kk, r = e - b * a.kk;
+    int b = e / kk, r = e - b * kk;
     float v = pkv[b * MAXM + r]; int i = pki[b * MAXM + r];
     if (better(v, i, lv[MAXM - 1], li[MAXM - 1])) {
       lv[MAXM - 1] = v; li[MAXM - 1] = i;
@@ -1257,6 +1250,28 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
     if (cur == wid) ++head;     // ids are unique: only the owner of the winner moves on
   }
   __syncthreads();
+}
+
+// Stand-alone early prediction: the merged top-k of one row's block lists written out (ids, and values when asked for).
+struct TopkMergeArgs {
+  const float* pk_val; const int32_t* pk_idx;   // [nblk][MAXM]
+  int nblk, kk, k;
+  int32_t* ids; float* vals;                    // [k]; vals may be null
+};
+
+// every workgroup merges the block candidates redundantly (they are few); winners land in win[]
+template <typename WT>
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
+  __shared__ float wv[SEL_THREADS / WAVE];
+  __shared__ int wi[SEL_THREADS / WAVE];
+  __shared__ int win[MAXM];
+  __shared__ float winv[MAXM];
+  __shared__ int s_midx, s_tok;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // merge of one row's block lists: the best nk by (value descending, id ascending) land in win[]
+  auto merge_row = [&](int prow, int nk) {
+    merge_block_lists(a.pk_val + (size_t)prow * a.pk_stride * MAXM, a.pk_idx + (size_t)prow * a.pk_stride * MAXM,
+                      a.nblk, a.kk, nk, wv, wi, win, winv);
   };
   merge_row(0, a.mode == 0 ? a.k : (a.samp_topk > 0 ? a.samp_topk : 1));
   if (a.mode == 0) {

@@ -73,3 +73,20 @@ def test_null_arguments():
     w = binding.Weights()
     h = ctypes.c_void_p()
     assert lib.ppd_create(ctypes.byref(d), ctypes.byref(w), 3, 2, None, ctypes.byref(h)) == -1
+
+
+def test_early_topk_rejects_bad_arguments():
+    lib = binding.load_library()
+    p = ctypes.c_void_p(256)      # never dereferenced: every case fails the argument checks
+    ok = dict(d_model=256, vocab=1000, norm=1, eps=1e-5, wdtype=1, k=3)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return lib.ppd_early_topk(a["d_model"], a["vocab"], a["norm"], a["eps"], a["wdtype"], a.get("g", p), None,
+                                  a.get("head", p), a.get("h", p), a["k"], a.get("ids", p), None, None, None)
+
+    assert call(d_model=250) == -1 and call(vocab=0) == -1 and call(norm=2) == -1 and call(wdtype=3) == -1
+    assert call(k=0) == -1 and call(k=9) == -1 and call(vocab=2, k=3) == -1
+    assert call(norm=0) == -1                      # LayerNorm without its bias
+    assert call(g=None) == -1 and call(head=None) == -1 and call(h=None) == -1 and call(ids=None) == -1
+    assert call(h=ctypes.c_void_p(260)) == -1      # misaligned row
