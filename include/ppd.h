@@ -242,6 +242,19 @@ int ppd_early_topk(int d_model, int vocab, int norm, float norm_eps, int wdtype,
                    const void *norm_b, const void *head, const float *h, int k, int32_t *ids_out,
                    float *vals_out, float *logits_out, void *hip_stream);
 
+/* ppd_early_topk for callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): same arguments, same kernels, same results, but the scratch is a fixed array inside the
+ * library's code object (288 KiB per GPU, held until the process ends) and the call neither allocates nor frees
+ * nor waits: it only queues its two launches on hip_stream, and the outputs are complete once that work has run.
+ * Limits: vocab <= 65536 (PPD_ELIMIT beyond; d_model is not limited).  The first call on a GPU looks up that
+ * GPU's copy of the array (make it outside any capture).  All calls on one GPU share the array and its contents
+ * survive from call to call (nothing in it needs clearing: every entry read is written first); calls whose work
+ * overlaps in time on one GPU -- different streams, or threads -- race on it: keep them on one stream or order
+ * them yourself. */
+int ppd_early_topk_noalloc(int d_model, int vocab, int norm, float norm_eps, int wdtype, const void *norm_g,
+                           const void *norm_b, const void *head, const float *h, int k, int32_t *ids_out,
+                           float *vals_out, float *logits_out, void *hip_stream);
+
 void ppd_destroy(ppd_ctx *ctx);
 
 const char *ppd_strerror(int code);

@@ -51,7 +51,7 @@ class Stats(ctypes.Structure):
 
 EXPORTS = ("ppd_create", "ppd_reset", "ppd_prefill", "ppd_step", "plain_greedy_step", "ppd_get_logits",
            "ppd_get_early_logits", "ppd_get_stats", "ppd_set_profiling", "ppd_set_graphs", "ppd_set_sampling", "ppd_get_kernel_time",
-           "ppd_time_ffn_in", "ppd_stream_read_probe", "ppd_early_topk", "ppd_destroy",
+           "ppd_time_ffn_in", "ppd_stream_read_probe", "ppd_early_topk", "ppd_early_topk_noalloc", "ppd_destroy",
            "ppd_strerror", "ppd_last_hip_error")
 
 _lib = None
@@ -85,6 +85,7 @@ def load_library() -> ctypes.CDLL:
     lib.ppd_time_ffn_in.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_stream_read_probe.argtypes = [vp, ctypes.c_uint64, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_early_topk.argtypes = [ci, ci, ci, ctypes.c_float, ci, vp, vp, vp, vp, ci, vp, vp, vp, vp]
+    lib.ppd_early_topk_noalloc.argtypes = lib.ppd_early_topk.argtypes
     lib.ppd_destroy.argtypes = [vp]
     lib.ppd_destroy.restype = None
     lib.ppd_strerror.argtypes = [ci]
@@ -151,6 +152,12 @@ def ppd_early_topk(h, norm_g, norm_b, head, k, norm, norm_eps=1e-5, want_logits=
     """Stand-alone early prediction on device tensors: (ids int32[k], logits of those float[k], all logits or None).
     h: float32 [d_model]; norm_g / norm_b / head: float32 or bfloat16 tensors of the model's weight type."""
     return _early_topk_call("ppd_early_topk", h, norm_g, norm_b, head, k, norm, norm_eps, want_logits, stream)
+
+
+def ppd_early_topk_noalloc(h, norm_g, norm_b, head, k, norm, norm_eps=1e-5, want_logits=False, stream=None):
+    """The same through the entry point that allocates nothing (fixed scratch array in the library; asynchronous:
+    the outputs are complete once the stream's work has run).  The output tensors are the caller's, made here."""
+    return _early_topk_call("ppd_early_topk_noalloc", h, norm_g, norm_b, head, k, norm, norm_eps, want_logits, stream)
 
 
 class PPD:

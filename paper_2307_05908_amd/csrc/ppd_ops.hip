@@ -8,6 +8,8 @@
 
 #include <string.h>
 
+#include <mutex>
+
 using namespace ppd;
 
 namespace ppd {
@@ -76,6 +78,37 @@ hipError_t early_topk_launch(const EarlyTopkPlan& p, int d_model, int vocab, int
   return hipGetLastError();
 }
 
+// ---- the variant that allocates nothing: its scratch is this array (one copy per GPU, held until the process ends)
+constexpr int NOALLOC_MAX_VOCAB = 65536;      // logits the array holds
+constexpr int NOALLOC_MAX_GRID = 512;         // per-workgroup top-k lists it holds (OPS_GMAX workgroups at most for such vocabularies)
+constexpr size_t NOALLOC_LOGITS_BYTES = (size_t)NOALLOC_MAX_VOCAB * sizeof(float);
+constexpr size_t NOALLOC_PK_BYTES = (size_t)NOALLOC_MAX_GRID * MAXM * sizeof(float);
+constexpr size_t NOALLOC_SCRATCH_BYTES = NOALLOC_LOGITS_BYTES + 2 * NOALLOC_PK_BYTES;   // 288 KiB
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[NOALLOC_MAX_DEVICES];     // device address of `scratch` on each GPU, looked up at the first call there
+
+// Device address of the current GPU's copy of the array (in host code the array's name is only a handle for this
+// lookup, never an address to pass on).
+hipError_t scratch_of_current_device(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -87,16 +120,37 @@ int ppd_early_topk(int d_model, int vocab, int norm, float norm_eps, int wdtype,
   int rc = early_topk_plan(d_model, vocab, norm, wdtype, norm_g, norm_b, head, h, k, ids_out, &p);
   if (rc) return rc;
   hipStream_t stream = (hipStream_t)hip_stream;
-  char* scratch = nullptr;
+  char* buf = nullptr;
   const size_t lb = logits_out ? 0 : p.logits_bytes;
-  hipError_t e = hipMalloc((void**)&scratch, lb + 2 * p.pk_bytes);
+  hipError_t e = hipMalloc((void**)&buf, lb + 2 * p.pk_bytes);
   if (e != hipSuccess) { set_global_hip_error((int)e); (void)hipGetLastError(); return e == hipErrorOutOfMemory ? PPD_ENOMEM : PPD_EHIP; }
-  float* logits = logits_out ? logits_out : (float*)scratch;
+  float* logits = logits_out ? logits_out : (float*)buf;
   e = early_topk_launch(p, d_model, vocab, norm, norm_eps, wdtype, norm_g, norm_b, head, h, k, logits,
-                        (float*)(scratch + lb), (int32_t*)(scratch + lb + p.pk_bytes), ids_out, vals_out, stream);
-  const hipError_t es = hipStreamSynchronize(stream);   // the scratch is freed below: the launches must be done with it
+                        (float*)(buf + lb), (int32_t*)(buf + lb + p.pk_bytes), ids_out, vals_out, stream);
+  const hipError_t es = hipStreamSynchronize(stream);   // the buffer is freed below: the launches must be done with it
   if (e == hipSuccess) e = es;
-  (void)hipFree(scratch);
+  (void)hipFree(buf);
+  if (e != hipSuccess) { set_global_hip_error((int)e); (void)hipGetLastError(); return PPD_EHIP; }
+  return PPD_OK;
+}
+
+int ppd_early_topk_noalloc(int d_model, int vocab, int norm, float norm_eps, int wdtype, const void* norm_g,
+                           const void* norm_b, const void* head, const float* h, int k, int32_t* ids_out,
+                           float* vals_out, float* logits_out, void* hip_stream) {
+  EarlyTopkPlan p;
+  int rc = early_topk_plan(d_model, vocab, norm, wdtype, norm_g, norm_b, head, h, k, ids_out, &p);
+  if (rc) return rc;
+  if (vocab > NOALLOC_MAX_VOCAB || p.grid > NOALLOC_MAX_GRID) return PPD_ELIMIT;
+  char* sp = nullptr;
+  hipError_t e = scratch_of_current_device(&sp);
+  if (e == hipSuccess) {
+    // nothing in the array has to start at zero: the GEMM writes every logit and the first k entries of every
+    // workgroup's list, and the merge reads only those
+    float* logits = logits_out ? logits_out : (float*)sp;
+    e = early_topk_launch(p, d_model, vocab, norm, norm_eps, wdtype, norm_g, norm_b, head, h, k, logits,
+                          (float*)(sp + NOALLOC_LOGITS_BYTES), (int32_t*)(sp + NOALLOC_LOGITS_BYTES + NOALLOC_PK_BYTES),
+                          ids_out, vals_out, (hipStream_t)hip_stream);
+  }
   if (e != hipSuccess) { set_global_hip_error((int)e); (void)hipGetLastError(); return PPD_EHIP; }
   return PPD_OK;
 }
