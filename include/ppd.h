@@ -163,7 +163,9 @@ int ppd_prefill(ppd_ctx *ctx, const int32_t *prompt, int n_prompt);
  * Writes the emitted token to out_tokens[0] (HOST, max_out >= 1) and returns
  * the number of tokens written: 1, or 0 once the previous token was EOS.
  * info (HOST, nullable) receives the round's record.  PPD_ECTX when position
- * t+1 would not fit in max_ctx.  Synchronous: the stream is idle on return.
+ * t+1 would not fit in max_ctx.  Synchronous: the round's record (token, match, candidates) is complete on
+ * return -- the call waits for the word the round's last kernel writes to pinned host memory after them; that
+ * kernel may still be retiring, and every later call on the context is ordered after it.
  * When exit_layer = d/2 and w->early_head is NULL (bf16 weights), the candidate
  * rows finish a round at the exit layer, so the round's final LM-head pass also
  * covers them; after a match the matching row's top-k are the next round's

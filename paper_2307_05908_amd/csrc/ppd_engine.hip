@@ -10,6 +10,9 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+#include <chrono>
+
 #include <new>
 #include <vector>
 
@@ -71,7 +74,8 @@ struct ppd_ctx {
   float2 *rope;          // [max_ctx][hd/2]
   DevState *ds;
   int32_t *prompt_dev;   // [max_ctx]
-  int32_t *host_result;  // pinned: token, match index, the round's candidates
+  int32_t *host_result;  // pinned: token, match index, the round's candidates, number of finished rounds
+  int32_t rounds_seen;   // value of that counter after the last round the host waited for
   int32_t *host_result_dev; // the same memory as the GPU sees it
   // captured rounds: 0 ppd round from layer 1, 1 ppd round after a match, 2 plain step, 3 ppd round after a
   // match whose candidates were predicted by the round before
@@ -573,13 +577,17 @@ int run_round(ppd_ctx* c, int kind, int pos) {
   if (c->dev_pos_pending != pos && (rc = set_state(c, pos, -1))) return rc;
   const int pmax = pos + (kind == 2 ? 0 : 1);
   if (c->use_graphs && !c->prof) {
-    const int nchunks = pmax / ATT_CHUNK + 1;
+    // Attention grid of the captured round: the chunks the round needs, rounded up to a power of two (at least 4,
+    // at most the cache's), so that a sequence re-captures a handful of times instead of every 64 positions;
+    // chunks past a row's position return at once.
+    int nchunks = 4;
+    while (nchunks < pmax / ATT_CHUNK + 1) nchunks *= 2;
+    if (nchunks > c->nchunk_max) nchunks = c->nchunk_max;
     if (c->graph[kind] && c->graph_chunks[kind] < nchunks) {
       HIPCHK(c, hipGraphExecDestroy(c->graph[kind]));
       c->graph[kind] = nullptr;
     }
     if (!c->graph[kind]) {
-      // capture with the attention grid sized for the whole 64-position chunk this round ends in
       hipGraph_t g = nullptr;
       HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed));
       rc = issue_round(c, kind, nchunks * ATT_CHUNK - 1);
@@ -596,7 +604,28 @@ int run_round(ppd_ctx* c, int kind, int pos) {
     if ((rc = issue_round(c, kind, pmax))) return rc;
   }
   c->dev_pos_pending = -1;                       // (unknown until the round is known to have run)
-  HIPCHK(c, hipStreamSynchronize(c->stream));
+  // The round's last kernel writes token and match index to pinned memory and then the count of finished rounds:
+  // poll that word instead of sleeping in a stream synchronisation (the wake-up costs more than a round's tail).
+  // Profiled rounds, and a round that does not report in time, take the synchronisation (which also surfaces errors).
+  {
+    volatile int32_t* seq = c->host_result + 2 + MAXM;
+    const int32_t want = c->rounds_seen + 1;
+    bool seen = false;
+    if (!c->prof) {
+      const auto t0 = std::chrono::steady_clock::now();
+      for (unsigned spin = 0; !seen; ++spin) {
+        seen = *seq == want;
+        if (!seen && (spin & 1023u) == 1023u &&
+            std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200)) break;
+      }
+    }
+    if (!seen) {
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+      if (*seq != want) { c->last_hip = (int)hipErrorUnknown; return PPD_EHIP; }
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    c->rounds_seen = want;
+  }
   c->dev_pos_pending = pos + 1;                  // left by the round's final selection
   if (c->prof) prof_collect(c);
   return PPD_OK;
@@ -729,7 +758,8 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
   alloc((void**)&c->ds, sizeof(DevState));
   alloc((void**)&c->prompt_dev, (size_t)d.max_ctx * sizeof(int32_t));
   if (d.pos == 1) alloc((void**)&c->rope, (size_t)d.max_ctx * (d.head_dim / 2) * sizeof(float2));
-  if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, (2 + MAXM) * sizeof(int32_t), hipHostMallocMapped);
+  if (e == hipSuccess) e = hipHostMalloc((void**)&c->host_result, (2 + MAXM + 1) * sizeof(int32_t), hipHostMallocMapped);
+  if (e == hipSuccess) memset(c->host_result, 0, (2 + MAXM + 1) * sizeof(int32_t));
   if (e == hipSuccess) e = hipHostGetDevicePointer((void**)&c->host_result_dev, c->host_result, 0);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking);
   c->cur = c->stream;
@@ -919,6 +949,7 @@ int plain_greedy_step(ppd_ctx* c, int32_t* out_token) {
 int ppd_get_logits(ppd_ctx* c, float* host_logits) {
   if (!c || !host_logits) return PPD_EINVAL;
   if (c->n_ctx < 0) return PPD_ESTATE;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(host_logits, c->logits, (size_t)c->d.vocab * sizeof(float), hipMemcpyDeviceToHost));
   return PPD_OK;
 }
@@ -929,6 +960,7 @@ int ppd_get_early_logits(ppd_ctx* c, float* host_logits) {
   // a round that started from a speculative prediction has its early logits in the half of early_spec that
   // its position's parity selects (the position of the last round's main token is n_ctx - 1)
   const float* src = c->last_kind == 3 ? c->early_spec + (size_t)((c->n_ctx - 1) & 1) * c->d.vocab : c->early_logits;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(host_logits, src, (size_t)c->d.vocab * sizeof(float), hipMemcpyDeviceToHost));
   return PPD_OK;
 }

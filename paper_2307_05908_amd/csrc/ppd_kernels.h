@@ -47,6 +47,7 @@ struct DevState {
   int32_t cand_next[MAXM]; // candidates of the next round, predicted at the end of a matching round
   int32_t sampled;    // final prediction drawn by the sampling kernel (sampling-based variants)
   int32_t pos_pending; // position of the next round: set explicitly, or left by a round's final selection (pos + 1)
+  int32_t seq;         // rounds finished since the context was created (the host waits for the next value)
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
@@ -908,7 +909,8 @@ struct SelectArgs {
   int k;
   int mode;             // 0: early top-k -> cand[0..k) + embed; 1: final arg max + verify + adopt
   DevState* ds;
-  int32_t* host_result; // device-visible pinned host memory: [0] token, [1] match_idx (mode 1), [2..2+k) candidates (mode 0)
+  int32_t* host_result; // device-visible pinned host memory: [0] token, [1] match_idx (mode 1), [2..2+k) candidates (mode 0),
+                        // [2 + MAXM] number of finished rounds, written after the rest (mode 1): the host polls it
   EmbedArgs emb;        // candidate rows (mode 0)
   // adoption (mode 1)
   float* h;                 // [1+k][d_model]: row 0 main, rows 1.. candidates
@@ -1314,6 +1316,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
     a.ds->result[0] = token; a.ds->result[1] = midx; a.ds->next_tok = token;
     a.ds->pos_pending = a.ds->pos + 1;      // the next round's position (its first launch takes it over)
     a.host_result[0] = token; a.host_result[1] = midx;
+    // the round's record is complete: let the host see it, then the new count
+    const int32_t seq = a.ds->seq + 1;
+    a.ds->seq = seq;
+    __threadfence_system();
+    *(volatile int32_t*)(a.host_result + 2 + MAXM) = seq;
   }
   if (midx < 0 || a.nb == 0) return;
   // adoption: block (l, which), l < nb, copies one layer's K or V tail; block (0,0) also the hidden row.

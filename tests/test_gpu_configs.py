@@ -11,7 +11,7 @@ import pytest
 
 import oracle
 import ppd_inputs as pi
-from gpu_common import TOL, gpu_generate, run_against_oracle
+from gpu_common import TOL, gpu_generate, run_against_oracle, tripwire
 from paper_2307_05908_amd import binding, tradeoff
 
 pytestmark = pytest.mark.gpu
@@ -92,6 +92,7 @@ def check_against_golden(name, gname, ks):
             resyncs += 1
             P.ppd_prefill(list(prompt) + [int(x) for x in otoks[:t + 1]])
     print(name, "plain vs stored oracle: max|dlogit|", worst, "resyncs", resyncs, flush=True)
+    assert worst <= tripwire(cfg), f"{name}: {worst:.3g} is within the tolerance but past the regression tripwire"
     for k in ks:
         Pk = binding.PPD(cfg, dev, k=k) if k != ks[0] else P
         Pk.ppd_prefill(prompt)
@@ -209,3 +210,27 @@ def test_llama13b_long_context():
     if not os.path.exists(os.path.join(GOLD, "llama13b.npz")):
         pytest.skip("no stored oracle outputs for llama13b")
     check_against_golden("llama13b", "llama13b", (3,))
+
+
+def test_llama7b_width_exit_layer_24_against_live_oracle():
+    """General exit layer (Algorithm 2) at full width: dbar = 24 of 32.  The candidates run layers 1..8; after a
+    match the main token resumes at layer 9 and runs alone to layer 24 before the next early prediction.  The
+    controlled-match-rate variant (late blocks damped) makes nearly every round match, so that path runs in
+    every round; the oracle runs live (short context), all logits compared."""
+    cfg, m, dev = model_on_gpu("llama7b_a0p1")
+    prompt = pi.make_prompt(cfg, 20)
+    o = oracle.Oracle(m, ctx_cap=40)
+    ro = o.ppd(prompt, 8, 3, 24, want_logits=True)
+    P = binding.PPD(cfg, dev, k=3, exit_layer=24)
+    r = run_against_oracle(P, prompt, "ppd", ro["tokens"], ro["final_logits"], ro["early_logits"], tol=2e-2)
+    print("llama7b dbar 24: max|dlogit|", r["max_err"], r["max_err_early"], "resyncs", r["resyncs"], "matches", r["matches"], flush=True)
+    assert r["matches"] >= 6 and ro["stats"]["matches"] >= 6
+    st = P.ppd_get_stats()
+    if r["resyncs"] == 0:
+        assert st["main_layer_rows"] == tradeoff.latency_of_runs(32, 24, 8, st["runs"])
+    Q = binding.PPD(cfg, dev, k=3)
+    ptoks, pz, _ = gpu_generate(Q, prompt, 8, "plain")
+    toks, z, _ = gpu_generate(P, prompt, 8, "ppd")
+    np.testing.assert_array_equal(toks, ptoks)
+    np.testing.assert_array_equal(z.view(np.uint32), pz.view(np.uint32))
+    o.close()
