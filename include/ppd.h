@@ -215,13 +215,15 @@ int ppd_set_profiling(ppd_ctx *ctx, int level);
 int ppd_set_graphs(ppd_ctx *ctx, int on);
 int ppd_get_kernel_time(ppd_ctx *ctx, int kernel_class, int groups, double *ms_total, uint64_t *launches);
 
-/* Measurement aid: launches the FFN-in GEMM (fused norm, first FFN matrix or the gate/up pair, activation) of
- * layers 1, 2, ... (reps launches, wrapping around) for the main row back to back between two HIP events
- * on the context's stream and reports the average milliseconds per launch (HOST output): the duration
- * of the kernel that bench.py prices against the HBM roofline, as it runs in a chain, without the event
- * pair that ppd_set_profiling(2) puts around every single launch.  Needs a prefilled context; overwrites
- * the activation rows, so the sequence state is gone afterwards (PPD_ESTATE until the next ppd_prefill). */
-int ppd_time_ffn_in(ppd_ctx *ctx, int reps, double *ms_per_launch);
+/* Measurement aid: launches the FFN-in GEMM (fused norm, first FFN matrix or the gate/up pair, activation)
+ * reps times back to back between two HIP events on the context's stream, every launch on other layers' weights
+ * than the one before, and reports the average milliseconds per launch (HOST output): the duration of the
+ * kernel that bench.py prices against the HBM roofline, as it runs in a chain, without the event pair that
+ * ppd_set_profiling(2) puts around every single launch.  groups = 2: the launch shape of a pipelined step (the
+ * main row on one layer's matrices and the k candidate rows on another's: two weight streams per launch);
+ * groups = 1: the main row alone (solo phase, plain steps).  Needs a prefilled context; overwrites the
+ * activation rows, so the sequence state is gone afterwards (PPD_ESTATE until the next ppd_prefill). */
+int ppd_time_ffn_in(ppd_ctx *ctx, int reps, int groups, double *ms_per_launch);
 
 /* Measurement aid (not part of the method): read `bytes` of DEVICE memory at dev_buf `iters` times with a
  * kernel that does nothing but non-temporal 16-byte loads (a few launch shapes, the best counts), and report the rate in GB/s (HOST

@@ -82,7 +82,7 @@ def load_library() -> ctypes.CDLL:
     lib.ppd_set_graphs.argtypes = [vp, ci]
     lib.ppd_set_sampling.argtypes = [vp, ci, ci, ctypes.c_double, ctypes.c_uint64]
     lib.ppd_get_kernel_time.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint64)]
-    lib.ppd_time_ffn_in.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double)]
+    lib.ppd_time_ffn_in.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_stream_read_probe.argtypes = [vp, ctypes.c_uint64, ci, ctypes.POINTER(ctypes.c_double)]
     lib.ppd_early_topk.argtypes = [ci, ci, ci, ctypes.c_float, ci, vp, vp, vp, vp, ci, vp, vp, vp, vp]
     lib.ppd_early_topk_noalloc.argtypes = lib.ppd_early_topk.argtypes
@@ -259,10 +259,11 @@ class PPD:
         """Final prediction by arg max (0), top-k sampling (1) or top-p sampling (2)."""
         self._chk(load_library().ppd_set_sampling(self._h, int(mode), int(top_k), float(top_p), int(seed)), "ppd_set_sampling")
 
-    def ppd_time_ffn_in(self, reps: int = 64) -> float:
-        """Average milliseconds per FFN-in GEMM launch in a back-to-back burst (invalidates the sequence)."""
+    def ppd_time_ffn_in(self, reps: int = 64, groups: int = 1) -> float:
+        """Average milliseconds per FFN-in GEMM launch in a back-to-back burst (invalidates the sequence);
+        groups = 2: the two-group launch of a pipelined step."""
         out = ctypes.c_double(0.0)
-        self._chk(load_library().ppd_time_ffn_in(self._h, reps, ctypes.byref(out)), "ppd_time_ffn_in")
+        self._chk(load_library().ppd_time_ffn_in(self._h, reps, groups, ctypes.byref(out)), "ppd_time_ffn_in")
         return float(out.value)
 
     def ppd_get_kernel_time(self) -> Dict[str, Dict[str, float]]:

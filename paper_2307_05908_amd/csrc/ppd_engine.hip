@@ -1006,8 +1006,8 @@ int ppd_get_kernel_time(ppd_ctx* c, int kernel_class, int groups, double* ms_tot
   return PPD_OK;
 }
 
-int ppd_time_ffn_in(ppd_ctx* c, int reps, double* ms_per_launch) {
-  if (!c || reps < 1 || !ms_per_launch) return PPD_EINVAL;
+int ppd_time_ffn_in(ppd_ctx* c, int reps, int groups, double* ms_per_launch) {
+  if (!c || reps < 1 || groups < 1 || groups > 2 || !ms_per_launch) return PPD_EINVAL;
   if (c->n_ctx < 0) return PPD_ESTATE;
   HIPCHK(c, hipStreamSynchronize(c->stream));
   hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -1020,12 +1020,14 @@ int ppd_time_ffn_in(ppd_ctx* c, int reps, double* ms_per_launch) {
   if (e == hipSuccess) {
     // one untimed launch per distinct layer first would warm nothing that matters (the weights do not fit
     // any cache); one warm-up launch for the code, then the timed burst
-    RowGroup g0{0, 1, 0, 0, false};
-    rc = run_layer(c, 1, &g0, 0, 4);
+    // groups == 2: the launch of a pipelined step (main row at one layer, the k candidate rows at another)
+    const int L = c->d.n_layers;
+    RowGroup g0[2] = {{0, 1, 0, 0, false}, {1 % L, c->k, 1, 1, true}};
+    rc = run_layer(c, groups, g0, 0, 4);
     if (!rc) e = hipEventRecord(e0, c->stream);
     for (int i = 0; i < reps && !rc && e == hipSuccess; ++i) {
-      RowGroup g{(1 + i) % c->d.n_layers, 1, 0, 0, false};
-      rc = run_layer(c, 1, &g, 0, 4);
+      RowGroup g[2] = {{(2 + 2 * i) % L, 1, 0, 0, false}, {(3 + 2 * i) % L, c->k, 1, 1, true}};
+      rc = run_layer(c, groups, g, 0, 4);
     }
     if (!rc && e == hipSuccess) e = hipEventRecord(e1, c->stream);
     if (!rc && e == hipSuccess) e = hipEventSynchronize(e1);

@@ -63,7 +63,7 @@ def test_null_arguments():
     assert lib.ppd_step(None, None, 1, None) == -1
     assert lib.plain_greedy_step(None, None) == -1
     out = ctypes.c_double(0.0)
-    assert lib.ppd_time_ffn_in(None, 4, ctypes.byref(out)) == -1
+    assert lib.ppd_time_ffn_in(None, 4, 1, ctypes.byref(out)) == -1
     assert lib.ppd_set_sampling(None, 1, 3, 1.0, 0) == -1
     assert lib.ppd_stream_read_probe(None, 1 << 20, 1, ctypes.byref(out)) == -1      # no buffer
     assert lib.ppd_stream_read_probe(ctypes.c_void_p(16), 24, 1, ctypes.byref(out)) == -1   # not a multiple of 16

@@ -189,6 +189,9 @@ def test_ffn_in_burst_timing_invalidates_the_sequence():
     P.ppd_prefill(prompt)
     ms = P.ppd_time_ffn_in(8)
     assert 0.0 < ms < 1.0
+    P.ppd_prefill(prompt)
+    ms2 = P.ppd_time_ffn_in(8, groups=2)             # the two-group launch of a pipelined step
+    assert 0.0 < ms2 < 1.0
     with pytest.raises(binding.PPDError) as ei:     # the activations were overwritten
         P.ppd_step()
     assert ei.value.code == -4
