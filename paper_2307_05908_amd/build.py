@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libppd.so")
 N_INST = 7
-DEPS = [os.path.join(CSRC, f) for f in ("ppd_engine.hip", "ppd_ops.hip", "ppd_inst.hip", "ppd_kernels.h", "ppd_launch.h")] + \
+DEPS = [os.path.join(CSRC, f) for f in ("ppd_engine.hip", "ppd_ops.hip", "ppd_prefill.hip", "ppd_prefill.h", "ppd_inst.hip", "ppd_kernels.h", "ppd_launch.h")] + \
        [os.path.join(os.path.dirname(HERE), "include", "ppd.h")]
 # -ffp-contract=off: every fused multiply-add in the kernels is an explicit fmaf, so a row's arithmetic
 # does not depend on which template instance it runs in.  Packed-fp32 code generation is switched off.
@@ -44,7 +44,8 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 0) -> str:
     jobs = jobs or min(8, os.cpu_count() or 4)
     with tempfile.TemporaryDirectory(prefix="ppd_build_") as tmp:
         units = [(os.path.join(CSRC, "ppd_engine.hip"), os.path.join(tmp, "engine.o"), [], verbose),
-                 (os.path.join(CSRC, "ppd_ops.hip"), os.path.join(tmp, "ops.o"), [], verbose)]
+                 (os.path.join(CSRC, "ppd_ops.hip"), os.path.join(tmp, "ops.o"), [], verbose),
+                 (os.path.join(CSRC, "ppd_prefill.hip"), os.path.join(tmp, "prefill.o"), [], verbose)]
         for i in range(N_INST):
             units.append((os.path.join(CSRC, "ppd_inst.hip"), os.path.join(tmp, f"inst{i}.o"), [f"-DPPD_INST={i}"], verbose))
         with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as ex:

@@ -5,6 +5,7 @@
 #include "../../include/ppd.h"
 #include "ppd_kernels.h"
 #include "ppd_launch.h"
+#include "ppd_prefill.h"
 
 #include <math.h>
 #include <stdlib.h>
@@ -65,6 +66,12 @@ struct ppd_ctx {
   int spec;
   int last_kind;         // kind of the last round (which buffer holds its early logits)
   int prefill_chunk;     // prompt positions per chunk
+  // compute-bound prompt pass (bf16 models, prompts of at least PREFILL_TILED_MIN rows): all rows at once through
+  // tiled MFMA GEMMs and causal attention over the cache; its buffers are made at the first such prompt
+  int prefill_tiled;
+  int pf_rows;           // rows the buffers below hold
+  float *pf_h, *pf_qkv, *pf_att, *pf_ffn;   // [pf_rows][d_model | 3 d_model | d_model | d_ff]
+  uint16_t *pf_xp;       // packed two-term rows of the widest GEMM input
   int dev_pos_pending;   // host mirror of the device state's pending position (-1: unknown)
   float* xn;             // [rows][d_model] normalised rows of a prompt chunk (norm_rows_kernel)
   // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
@@ -649,13 +656,86 @@ void account_round(ppd_ctx* c, int kind, int pos) {
 void free_all(ppd_ctx* c) {
   for (int i = 0; i < 4; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
-                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->xn, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
+                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->xn, c->pf_h, c->pf_qkv, c->pf_att, c->pf_ffn, c->pf_xp, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   if (c->join_ev) (void)hipEventDestroy(c->join_ev);
   if (c->stream) (void)hipStreamDestroy(c->stream);
+}
+
+constexpr int PREFILL_TILED_MIN = 32;
+
+// The whole prompt (rows 0 .. rows-1 at positions 0 .. rows-1) through all layers: fills the cache.
+int prefill_tiled(ppd_ctx* c, int rows) {
+  const ppd_model_dims& d = c->d;
+  const int dm = d.d_model, F = d.d_ff;
+  const bool bias = d.has_bias != 0, swiglu = d.act == 2;
+  if (rows > c->pf_rows) {
+    void* old[] = {c->pf_h, c->pf_qkv, c->pf_att, c->pf_ffn, c->pf_xp};
+    for (void* p : old) (void)hipFree(p);
+    c->pf_h = c->pf_qkv = c->pf_att = c->pf_ffn = nullptr; c->pf_xp = nullptr; c->pf_rows = 0;
+    const size_t R = (size_t)((rows + 63) / 64) * 64;
+    const int kmax = F > dm ? F : dm;
+    HIPCHK(c, hipMalloc((void**)&c->pf_h, R * dm * sizeof(float)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_qkv, R * 3 * dm * sizeof(float)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_att, R * dm * sizeof(float)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_ffn, R * F * sizeof(float)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_xp, packed_bytes((int)R, kmax)));
+    c->pf_rows = (int)R;
+  }
+  int rc = set_state(c, 0, -1);
+  if (rc) return rc;
+  {
+    EmbedArgs ea = embed_args(c, c->prompt_dev, rows, 0, 0);
+    ea.h = c->pf_h; ea.pos_step = 1;
+    hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3((dm + 255) / 256, rows), dim3(256), 0, c->cur, ea);
+    HIPCHK(c, hipGetLastError());
+  }
+  const int MT = (rows + 15) / 16;
+  auto pack = [&](const float* X, int ld, int K, const void* g, const void* b, int norm) -> hipError_t {
+    PackArgs p; memset(&p, 0, sizeof p);
+    p.X = X; p.ld = ld; p.M = rows; p.K = K; p.KT = (K + 31) / 32; p.MT = MT; p.g = g; p.b = b; p.norm = norm; p.eps = d.norm_eps;
+    p.out = c->pf_xp;
+    return launch_pack_rows(c->cur, p);
+  };
+  auto gemm = [&](const void* P, int K, int n0, int n1, int n2, bool paired, const void* b0, const void* b1, const void* b2,
+                  const float* rsd, float* Y, int ldy, int act) -> hipError_t {
+    PGemmArgs g; memset(&g, 0, sizeof g);
+    g.Xp = c->pf_xp; g.P = P; g.B[0] = b0; g.B[1] = b1; g.B[2] = b2; g.Rsd = rsd; g.Y = Y;
+    g.M = rows; g.MT = MT; g.KT = (K + 31) / 32;
+    g.N[0] = n0; g.N[1] = n1; g.N[2] = n2; g.ntot = paired ? n0 : n0 + n1 + n2;
+    g.NT = paired ? (n0 + 7) / 8 : (g.ntot + 15) / 16;
+    g.ldy = ldy; g.act = act;
+    return launch_pgemm(c->cur, g, paired);
+  };
+  for (int l = 0; l < d.n_layers; ++l) {
+    const LayerW& w = c->L[l];
+    const ppd_ctx::LayerP& P = c->LP[l];
+    HIPCHK(c, pack(c->pf_h, dm, dm, w.ln1_g, d.norm == 0 ? w.ln1_b : nullptr, d.norm));
+    HIPCHK(c, gemm(P.qkv, dm, dm, dm, dm, false, bias ? w.bq : nullptr, bias ? w.bk : nullptr, bias ? w.bv : nullptr,
+                   nullptr, c->pf_qkv, 3 * dm, 0));
+    {
+      ChunkKvArgs kv; memset(&kv, 0, sizeof kv);
+      kv.qkv = c->pf_qkv; kv.Kc = (float*)(c->Kc + (size_t)l * cache_layer_bytes(c)); kv.Vc = (float*)(c->Vc + (size_t)l * cache_layer_bytes(c));
+      kv.rope = d.pos == 1 ? c->rope : nullptr; kv.ds = c->ds; kv.HD = d.head_dim; kv.d_model = dm; kv.max_ctx = d.max_ctx;
+      hipLaunchKernelGGL(chunk_kv_kernel, dim3(rows, d.n_heads), dim3(d.head_dim), 0, c->cur, kv);
+      HIPCHK(c, hipGetLastError());
+      PAttnArgs pa; memset(&pa, 0, sizeof pa);
+      pa.qkv = c->pf_qkv; pa.Kc = kv.Kc; pa.Vc = kv.Vc; pa.rope = kv.rope; pa.ds = c->ds; pa.out = c->pf_att;
+      pa.M = rows; pa.H = d.n_heads; pa.d_model = dm; pa.max_ctx = d.max_ctx; pa.scale = 1.0f / sqrtf((float)d.head_dim);
+      HIPCHK(c, launch_pattn(c->cur, pa, d.head_dim));
+    }
+    HIPCHK(c, pack(c->pf_att, dm, dm, nullptr, nullptr, -1));
+    HIPCHK(c, gemm(P.o, dm, dm, 0, 0, false, bias ? w.bo : nullptr, nullptr, nullptr, c->pf_h, c->pf_h, dm, 0));
+    HIPCHK(c, pack(c->pf_h, dm, dm, w.ln2_g, d.norm == 0 ? w.ln2_b : nullptr, d.norm));
+    if (swiglu) HIPCHK(c, gemm(P.fin, dm, F, F, 0, true, bias ? w.b_in : nullptr, nullptr, nullptr, nullptr, c->pf_ffn, F, 0));
+    else HIPCHK(c, gemm(P.fin, dm, F, 0, 0, false, bias ? w.b_in : nullptr, nullptr, nullptr, nullptr, c->pf_ffn, F, d.act == 0 ? 1 : 2));
+    HIPCHK(c, pack(c->pf_ffn, F, F, nullptr, nullptr, -1));
+    HIPCHK(c, gemm(P.fout, F, dm, 0, 0, false, bias ? w.b_out : nullptr, nullptr, nullptr, c->pf_h, c->pf_h, dm, 0));
+  }
+  return PPD_OK;
 }
 
 int env_int(const char* name, int dflt) {
@@ -723,6 +803,9 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     const int cap = d.wdtype == 1 ? PREFILL_CHUNK : PREFILL_CHUNK_FP32;
     c->prefill_chunk = env_int("PPD_PREFILL_CHUNK", cap);
     if (c->prefill_chunk > cap) c->prefill_chunk = cap;
+    // the compute-bound pass takes prompts of bf16 models unless the row-chunk path is asked for (PPD_PREFILL_CHUNK
+    // set, or PPD_PREFILL_TILED=2)
+    c->prefill_tiled = d.wdtype == 1 && !getenv("PPD_PREFILL_CHUNK") && env_int("PPD_PREFILL_TILED", 1) != 2;
   }
   c->gmax1 = 512;
   c->gmax2 = 256;
@@ -874,7 +957,9 @@ int ppd_prefill(ppd_ctx* c, const int32_t* prompt, int n_prompt) {
   // positions 0 .. n_prompt-2 in chunks of consecutive positions: every row's arithmetic is that of a
   // token-by-token pass (PPD_PREFILL_CHUNK=1 runs exactly that), the weights are streamed once per chunk
   const int chunk = c->prefill_chunk;
-  for (int i = 0; i + 1 < n_prompt && !rc; i += chunk) {
+  const bool tiled = c->prefill_tiled && n_prompt - 1 >= PREFILL_TILED_MIN;
+  if (tiled) rc = prefill_tiled(c, n_prompt - 1);
+  for (int i = 0; !tiled && i + 1 < n_prompt && !rc; i += chunk) {
     const int m = n_prompt - 1 - i < chunk ? n_prompt - 1 - i : chunk;
     rc = set_state(c, i, -1);
     if (!rc) {

@@ -295,6 +295,7 @@ def test_prompt_in_chunks_is_token_by_token_bit_exact(name, monkeypatch):
         return toks, z, ptoks, pz
 
     lengths = sorted({2, 3, 9, 10, cfg.n_prompt, min(cfg.max_ctx - 8, 70), min(cfg.max_ctx - 8, 130)})
+    monkeypatch.setenv("PPD_PREFILL_TILED", "2")     # (longer prompts of bf16 models would take the compute-bound pass)
     got = {n: run(n) for n in lengths}
     monkeypatch.setenv("PPD_PREFILL_CHUNK", "16")
     got16 = {n: run(n) for n in lengths}
@@ -350,3 +351,36 @@ def test_separate_early_head_matches_oracle_and_keeps_the_output(family, near):
         assert np.abs(Pd.ppd_get_early_logits() - P.ppd_get_early_logits()).max() > 1e-2
         Pd.close()
         P.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["llama_long", "opt_long"])
+def test_compute_bound_prompt_pass_against_oracle_and_row_chunks(name, monkeypatch):
+    """Prompts of bf16 models from 32 rows on go through tiled MFMA GEMMs and causal attention over the cache, all
+    rows at once.  Other tiles and summation trees than the decode kernels: the cache is close to, not identical
+    with, the row-chunk path's.  Checked: the logits of the next tokens against the oracle (teacher-forced, tolerance
+    2e-2 and the tripwire) for prompt lengths with ragged 16- and 64-row tiles, against the row-chunk path (a few
+    1e-5 apart at most), and PPD == plain greedy bit for bit from either cache."""
+    cfg = SMALL[name]
+    m = pi.make_model(cfg)
+    dev = binding.upload_model(m)
+    o = oracle.Oracle(m)
+    worst = 0.0
+    for n_prompt in (33, 64, 65, 81, 128, 129, cfg.n_prompt):
+        prompt = pi.make_prompt(cfg, n_prompt)
+        ro = o.ppd(prompt, 6, 3, cfg.exit_layer, want_logits=True)
+        monkeypatch.setenv("PPD_PREFILL_TILED", "1")
+        P = binding.PPD(cfg, dev, k=3)
+        r = run_against_oracle(P, prompt, "ppd", ro["tokens"], ro["final_logits"], ro["early_logits"], tol=TOL[cfg.wdtype])
+        toks, z, _ = gpu_generate(P, prompt, 6, "ppd")
+        ptoks, pz, _ = gpu_generate(P, prompt, 6, "plain")
+        np.testing.assert_array_equal(toks, ptoks)
+        np.testing.assert_array_equal(z.view(np.uint32), pz.view(np.uint32))
+        P.close()
+        monkeypatch.setenv("PPD_PREFILL_TILED", "2")
+        Q = binding.PPD(cfg, dev, k=3)
+        qtoks, qz, _ = gpu_generate(Q, prompt, 6, "ppd")
+        Q.close()
+        worst = max(worst, float(np.abs(z - qz).max()), r["max_err"])
+        assert np.abs(z - qz).max() <= 1e-4
+    print(name, "compute-bound prompt pass: worst |dlogit| vs oracle / row chunks", worst, flush=True)
