@@ -70,8 +70,10 @@ struct ppd_ctx {
   // tiled MFMA GEMMs and causal attention over the cache; its buffers are made at the first such prompt
   int prefill_tiled;
   int pf_rows;           // rows the buffers below hold
-  float *pf_h, *pf_qkv, *pf_att, *pf_ffn;   // [pf_rows][d_model | 3 d_model | d_model | d_ff]
-  uint16_t *pf_xp;       // packed two-term rows of the widest GEMM input
+  float *pf_h, *pf_qkv;  // [pf_rows][d_model | 3 d_model]
+  uint16_t *pf_xp;       // packed two-term rows: the normalised hidden rows (input of the QKV and FFN-in GEMMs),
+  uint16_t *pf_xa;       // the attention outputs (written by the attention kernel),
+  uint16_t *pf_xf;       // the feed-forward activations (written by the FFN-in GEMM; zero beyond d_ff)
   int dev_pos_pending;   // host mirror of the device state's pending position (-1: unknown)
   float* xn;             // [rows][d_model] normalised rows of a prompt chunk (norm_rows_kernel)
   // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
@@ -656,7 +658,7 @@ void account_round(ppd_ctx* c, int kind, int pos) {
 void free_all(ppd_ctx* c) {
   for (int i = 0; i < 4; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
-                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->xn, c->pf_h, c->pf_qkv, c->pf_att, c->pf_ffn, c->pf_xp, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
+                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->xn, c->pf_h, c->pf_qkv, c->pf_xp, c->pf_xa, c->pf_xf, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
@@ -673,18 +675,19 @@ int prefill_tiled(ppd_ctx* c, int rows) {
   const int dm = d.d_model, F = d.d_ff;
   const bool bias = d.has_bias != 0, swiglu = d.act == 2;
   if (rows > c->pf_rows) {
-    void* old[] = {c->pf_h, c->pf_qkv, c->pf_att, c->pf_ffn, c->pf_xp};
+    void* old[] = {c->pf_h, c->pf_qkv, c->pf_xp, c->pf_xa, c->pf_xf};
     for (void* p : old) (void)hipFree(p);
-    c->pf_h = c->pf_qkv = c->pf_att = c->pf_ffn = nullptr; c->pf_xp = nullptr; c->pf_rows = 0;
+    c->pf_h = c->pf_qkv = nullptr; c->pf_xp = c->pf_xa = c->pf_xf = nullptr; c->pf_rows = 0;
     const size_t R = (size_t)((rows + 63) / 64) * 64;
-    const int kmax = F > dm ? F : dm;
     HIPCHK(c, hipMalloc((void**)&c->pf_h, R * dm * sizeof(float)));
     HIPCHK(c, hipMalloc((void**)&c->pf_qkv, R * 3 * dm * sizeof(float)));
-    HIPCHK(c, hipMalloc((void**)&c->pf_att, R * dm * sizeof(float)));
-    HIPCHK(c, hipMalloc((void**)&c->pf_ffn, R * F * sizeof(float)));
-    HIPCHK(c, hipMalloc((void**)&c->pf_xp, packed_bytes((int)R, kmax)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_xp, packed_bytes((int)R, dm)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_xa, packed_bytes((int)R, dm)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_xf, packed_bytes((int)R, F)));
     c->pf_rows = (int)R;
   }
+  // (the packed layouts depend on the row count: the padding columns of the activations are cleared per prompt)
+  HIPCHK(c, hipMemsetAsync(c->pf_xf, 0, packed_bytes(rows, F), c->cur));
   int rc = set_state(c, 0, -1);
   if (rc) return rc;
   {
@@ -700,10 +703,10 @@ int prefill_tiled(ppd_ctx* c, int rows) {
     p.out = c->pf_xp;
     return launch_pack_rows(c->cur, p);
   };
-  auto gemm = [&](const void* P, int K, int n0, int n1, int n2, bool paired, const void* b0, const void* b1, const void* b2,
-                  const float* rsd, float* Y, int ldy, int act) -> hipError_t {
+  auto gemm = [&](const uint16_t* Xp, const void* P, int K, int n0, int n1, int n2, bool paired, const void* b0, const void* b1, const void* b2,
+                  const float* rsd, float* Y, int ldy, int act, uint16_t* Yp = nullptr) -> hipError_t {
     PGemmArgs g; memset(&g, 0, sizeof g);
-    g.Xp = c->pf_xp; g.P = P; g.B[0] = b0; g.B[1] = b1; g.B[2] = b2; g.Rsd = rsd; g.Y = Y;
+    g.Xp = Xp; g.P = P; g.Yp = Yp; g.KTp = (n0 + 31) / 32; g.B[0] = b0; g.B[1] = b1; g.B[2] = b2; g.Rsd = rsd; g.Y = Y;
     g.M = rows; g.MT = MT; g.KT = (K + 31) / 32;
     g.N[0] = n0; g.N[1] = n1; g.N[2] = n2; g.ntot = paired ? n0 : n0 + n1 + n2;
     g.NT = paired ? (n0 + 7) / 8 : (g.ntot + 15) / 16;
@@ -714,7 +717,7 @@ int prefill_tiled(ppd_ctx* c, int rows) {
     const LayerW& w = c->L[l];
     const ppd_ctx::LayerP& P = c->LP[l];
     HIPCHK(c, pack(c->pf_h, dm, dm, w.ln1_g, d.norm == 0 ? w.ln1_b : nullptr, d.norm));
-    HIPCHK(c, gemm(P.qkv, dm, dm, dm, dm, false, bias ? w.bq : nullptr, bias ? w.bk : nullptr, bias ? w.bv : nullptr,
+    HIPCHK(c, gemm(c->pf_xp, P.qkv, dm, dm, dm, dm, false, bias ? w.bq : nullptr, bias ? w.bk : nullptr, bias ? w.bv : nullptr,
                    nullptr, c->pf_qkv, 3 * dm, 0));
     {
       ChunkKvArgs kv; memset(&kv, 0, sizeof kv);
@@ -723,17 +726,15 @@ int prefill_tiled(ppd_ctx* c, int rows) {
       hipLaunchKernelGGL(chunk_kv_kernel, dim3(rows, d.n_heads), dim3(d.head_dim), 0, c->cur, kv);
       HIPCHK(c, hipGetLastError());
       PAttnArgs pa; memset(&pa, 0, sizeof pa);
-      pa.qkv = c->pf_qkv; pa.Kc = kv.Kc; pa.Vc = kv.Vc; pa.rope = kv.rope; pa.ds = c->ds; pa.out = c->pf_att;
+      pa.qkv = c->pf_qkv; pa.Kc = kv.Kc; pa.Vc = kv.Vc; pa.rope = kv.rope; pa.ds = c->ds; pa.outp = c->pf_xa;
       pa.M = rows; pa.H = d.n_heads; pa.d_model = dm; pa.max_ctx = d.max_ctx; pa.scale = 1.0f / sqrtf((float)d.head_dim);
       HIPCHK(c, launch_pattn(c->cur, pa, d.head_dim));
     }
-    HIPCHK(c, pack(c->pf_att, dm, dm, nullptr, nullptr, -1));
-    HIPCHK(c, gemm(P.o, dm, dm, 0, 0, false, bias ? w.bo : nullptr, nullptr, nullptr, c->pf_h, c->pf_h, dm, 0));
+    HIPCHK(c, gemm(c->pf_xa, P.o, dm, dm, 0, 0, false, bias ? w.bo : nullptr, nullptr, nullptr, c->pf_h, c->pf_h, dm, 0));
     HIPCHK(c, pack(c->pf_h, dm, dm, w.ln2_g, d.norm == 0 ? w.ln2_b : nullptr, d.norm));
-    if (swiglu) HIPCHK(c, gemm(P.fin, dm, F, F, 0, true, bias ? w.b_in : nullptr, nullptr, nullptr, nullptr, c->pf_ffn, F, 0));
-    else HIPCHK(c, gemm(P.fin, dm, F, 0, 0, false, bias ? w.b_in : nullptr, nullptr, nullptr, nullptr, c->pf_ffn, F, d.act == 0 ? 1 : 2));
-    HIPCHK(c, pack(c->pf_ffn, F, F, nullptr, nullptr, -1));
-    HIPCHK(c, gemm(P.fout, F, dm, 0, 0, false, bias ? w.b_out : nullptr, nullptr, nullptr, c->pf_h, c->pf_h, dm, 0));
+    if (swiglu) HIPCHK(c, gemm(c->pf_xp, P.fin, dm, F, F, 0, true, bias ? w.b_in : nullptr, nullptr, nullptr, nullptr, nullptr, F, 0, c->pf_xf));
+    else HIPCHK(c, gemm(c->pf_xp, P.fin, dm, F, 0, 0, false, bias ? w.b_in : nullptr, nullptr, nullptr, nullptr, nullptr, F, d.act == 0 ? 1 : 2, c->pf_xf));
+    HIPCHK(c, gemm(c->pf_xf, P.fout, F, dm, 0, 0, false, bias ? w.b_out : nullptr, nullptr, nullptr, c->pf_h, c->pf_h, dm, 0));
   }
   return PPD_OK;
 }

@@ -126,7 +126,26 @@ struct PGemmArgs {
   int ldy;
   int act;              // 0 none, 1 GELU, 2 ReLU (paired launches apply SwiGLU)
   int NB, MB;           // workgroup grid: NB blocks of 4 * TN tiles along the outputs, MB blocks of PG_TM tiles along the rows
+  // the outputs in packed two-term form instead of Y (they are the next GEMM's rows: the feed-forward activations):
+  // [2][MT][KTp][64][8]; only outputs below ntot are written, the padding columns of the buffer stay as they are (zero)
+  uint16_t* Yp; int KTp;
 };
+
+// four consecutive outputs n0 .. n0 + 3 (n0 a multiple of 4) of row m into the packed form: half of an 8-column piece
+__device__ __forceinline__ void put_packed4(uint16_t* out, size_t plane_elems, int KT, int m, int n0, const float (&y)[4]) {
+  uint32_t hp[2], lp[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    hp[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){y[2 * e], y[2 * e + 1]}, bf16x2));
+    const float r0 = y[2 * e] - __uint_as_float(hp[e] << 16), r1 = y[2 * e + 1] - __uint_as_float(hp[e] & 0xffff0000u);
+    lp[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){r0, r1}, bf16x2));
+  }
+  const int c8 = n0 >> 3;
+  const size_t o = (((size_t)(m >> 4) * KT + (c8 >> 2)) * 64 + (m & 15) + 16 * (c8 & 3)) * 8 + ((n0 >> 2) & 1) * 4;
+  *(uint2*)(out + o) = make_uint2(hp[0], hp[1]);
+  *(uint2*)(out + plane_elems + o) = make_uint2(lp[0], lp[1]);
+}
+
 
 // Workgroup b of the launch: an eighth of the output blocks per XCD (workgroups go round the XCDs in launch
 // order), and all row blocks of an output block one after the other on the same XCD, so that a weight block is
@@ -216,6 +235,13 @@ __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
           const float bg = B0 ? bf16_to_f32(B0[n]) : 0.f, bu = B1 ? bf16_to_f32(B1[n]) : 0.f;
           y[q] = silu(v[q] + bg) * (u[q] + bu);
         }
+        if (a.Yp) {
+          if (n0 >= a.ntot) continue;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) if (n0 + q >= a.ntot) y[q] = 0.f;
+          put_packed4(a.Yp, (size_t)a.MT * a.KTp * 512, a.KTp, m, n0, y);
+          continue;
+        }
         float* py = a.Y + (size_t)m * a.ldy + n0;
         if (n0 + 3 < a.ntot) *(float4*)py = make_float4(y[0], y[1], y[2], y[3]);
         else for (int q = 0; q < 4; ++q) if (n0 + q < a.ntot) py[q] = y[q];
@@ -238,6 +264,13 @@ __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
           if (a.Rsd) t += a.Rsd[(size_t)m * a.ldy + n];
           y[q] = t;
         }
+        if (a.Yp) {
+          if (n0 >= a.ntot) continue;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) if (n0 + q >= a.ntot) y[q] = 0.f;
+          put_packed4(a.Yp, (size_t)a.MT * a.KTp * 512, a.KTp, m, n0, y);
+          continue;
+        }
         float* py = a.Y + (size_t)m * a.ldy + n0;
         if (n0 + 3 < a.ntot) *(float4*)py = make_float4(y[0], y[1], y[2], y[3]);
         else for (int q = 0; q < 4; ++q) if (n0 + q < a.ntot) py[q] = y[q];
@@ -256,7 +289,7 @@ struct PAttnArgs {
   const float* Kc; const float* Vc;   // this layer's cache
   const float2* rope;   // [max_ctx][hd / 2] or null
   const DevState* ds;   // row 0 sits at position ds->pos
-  float* out;           // [M][d_model]
+  uint16_t* outp;       // the outputs in packed two-term form [2][MT][d_model / 32][64][8] (rows of the output projection)
   int M, H, d_model, max_ctx;
   float scale;
 };
@@ -353,10 +386,12 @@ __global__ __launch_bounds__(256) void pattn_kernel(PAttnArgs a) {
   }
   if (mrow < a.M) {
     const float inv = 1.0f / l;
-    float* po = a.out + (size_t)mrow * a.d_model + (size_t)h * HD + 4 * bc;
+    const int MT = (a.M + 15) / 16, KT = a.d_model / 32;
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
-      *(float4*)(po + 16 * s) = make_float4(oacc[s][0] * inv, oacc[s][1] * inv, oacc[s][2] * inv, oacc[s][3] * inv);
+    for (int s = 0; s < NS; ++s) {
+      const float y[4] = {oacc[s][0] * inv, oacc[s][1] * inv, oacc[s][2] * inv, oacc[s][3] * inv};
+      put_packed4(a.outp, (size_t)MT * KT * 512, KT, mrow, h * HD + 16 * s + 4 * bc, y);
+    }
   }
 }
 
