@@ -28,11 +28,25 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
-# HBM bytes per launch of the roofline kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel of known
-# size), keyed by (configuration, k): a property of the build it was collected on, named in `traffic_build`; the
-# collection is described in profiles/.  None: not collected for this configuration.
-MEASURED_TRAFFIC = {}
-TRAFFIC_BUILD = None
+# HBM bytes per launch of the roofline kernel (the two-group FFN-in GEMM) from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled
+# by a copy kernel of known size, keyed by (configuration, k); collected with the counter probe on the C ABI
+# (paper_2307_05908_amd/ppd_pmc_probe), see profiles/.  A property of the kernel source it was collected on.
+MEASURED_TRAFFIC = {("llama7b", 3): 361.75e6}
+# sha1 of csrc/ppd_kernels.h when the counters were collected: a changed kernel source voids the figure (null is printed)
+TRAFFIC_KERNELS_SHA1 = "f5a89d12e3b9190c815472e09b4e06c36a5c6789"
+TRAFFIC_SOURCE = "profiles/llama7b_ppd_k3_traffic.txt"
+
+
+def measured_traffic(cfg_name, k):
+    import hashlib
+    try:
+        h = hashlib.sha1(open(os.path.join(ROOT, "paper_2307_05908_amd", "csrc", "ppd_kernels.h"), "rb").read()).hexdigest()
+    except OSError:
+        return None, None
+    v = MEASURED_TRAFFIC.get((cfg_name, k))
+    if v is None or h != TRAFFIC_KERNELS_SHA1:
+        return None, None
+    return v, TRAFFIC_SOURCE
 
 
 def kernel_bytes(cfg, pi, ctx, k):
@@ -286,7 +300,7 @@ def main():
         roof = {"bound": "hbm",
                 "kernel": kname + ", the two-group launch of a pipelined step: main row on one layer's matrices, the %d candidate rows on another's" % k,
                 "achieved": round(ach2, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach2 / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get((cfg.name, k)), "traffic_build": TRAFFIC_BUILD if MEASURED_TRAFFIC.get((cfg.name, k)) else None,
+                "traffic": measured_traffic(cfg.name, k)[0], "traffic_source": measured_traffic(cfg.name, k)[1],
                 "bytes_per_launch": 2 * ffn_in_bytes, "avg_launch_us": round(burst2_ms * 1e3, 2),
                 "timing": "HIP events around a burst of %d back-to-back launches on the library's stream, other layers' weights in every launch" % (2 * cfg.n_layers),
                 "stream_read_GBps": round(stream_gbs, 1), "frac_of_stream_read": round(ach2 / stream_gbs, 4),

@@ -13,8 +13,9 @@ import tempfile
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libppd.so")
+PROBE_PATH = os.path.join(HERE, "ppd_pmc_probe")
 N_INST = 7
-DEPS = [os.path.join(CSRC, f) for f in ("ppd_engine.hip", "ppd_ops.hip", "ppd_prefill.hip", "ppd_prefill.h", "ppd_inst.hip", "ppd_kernels.h", "ppd_launch.h")] + \
+DEPS = [os.path.join(CSRC, f) for f in ("ppd_engine.hip", "ppd_ops.hip", "ppd_pmc_probe.cpp", "ppd_prefill.hip", "ppd_prefill.h", "ppd_inst.hip", "ppd_kernels.h", "ppd_launch.h")] + \
        [os.path.join(os.path.dirname(HERE), "include", "ppd.h")]
 # -ffp-contract=off: every fused multiply-add in the kernels is an explicit fmaf, so a row's arithmetic
 # does not depend on which template instance it runs in.  Packed-fp32 code generation is switched off.
@@ -53,6 +54,12 @@ def build(force: bool = True, verbose: bool = False, jobs: int = 0) -> str:
                 if out.strip() and verbose:
                     print(out)
         cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + [u[1] for u in units]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+        # the counter probe: a small program on the C ABI (no Python), for rocprofv3 --pmc runs
+        cmd = ["hipcc", "-O2", "-std=c++17", "--offload-arch=gfx950", "-o", PROBE_PATH, os.path.join(CSRC, "ppd_pmc_probe.cpp"),
+               "-L" + HERE, "-lppd", "-Wl,-rpath,$ORIGIN"]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

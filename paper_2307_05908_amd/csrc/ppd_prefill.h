@@ -22,6 +22,10 @@ namespace ppd {
 constexpr int PG_THREADS = 256;     // 4 waves
 constexpr int PG_WAVES = PG_THREADS / WAVE;
 constexpr int PG_TM = 4;            // 16-row tiles of the prompt per wave: 64 rows per workgroup
+#ifndef PPD_PG_NBUF
+#define PPD_PG_NBUF 4
+#endif
+constexpr int PG_NBUF = PPD_PG_NBUF;   // register buffers of operand blocks per wave
 
 // ---- rows -> packed two-term operand blocks
 // Block (mt, kt) holds rows 16 mt .. +15, columns 32 kt .. +31 as 64 lanes x 8 bf16: lane i + 16 c = row i, columns
@@ -176,9 +180,10 @@ __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
   for (int i = 0; i < TN; ++i)
 #pragma unroll
     for (int j = 0; j < PG_TM; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  u32x4 wa[2][TN], xh[2][PG_TM], xl[2][PG_TM];
+  // PG_NBUF register buffers: the blocks of the next PG_NBUF - 1 reduction steps are in flight while one is multiplied
+  u32x4 wa[PG_NBUF][TN], xh[PG_NBUF][PG_TM], xl[PG_NBUF][PG_TM];
   auto fetch = [&](int kt, int buf) {
-    const size_t o = (size_t)kt * 1024;
+    const size_t o = (size_t)(kt < KT ? kt : KT - 1) * 1024;       // (requests past the end repeat the last block; unused)
 #pragma unroll
     for (int t = 0; t < TN; ++t) wa[buf][t] = *(const u32x4*)(wbase[t] + o);
 #pragma unroll
@@ -197,15 +202,22 @@ __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
       for (int j = 0; j < PG_TM; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wa[buf][i]), __builtin_bit_cast(bf16x8, xl[buf][j]), acc[i][j], 0, 0, 0);
   };
-  fetch(0, 0);
+#pragma unroll
+  for (int p = 0; p < PG_NBUF - 1; ++p) fetch(p, p);
   int kt = 0;
-  for (; kt + 2 <= KT; kt += 2) {
-    fetch(kt + 1, 1);
-    mac(0);
-    fetch(kt + 2 < KT ? kt + 2 : kt + 1, 0);     // (the last request of an even reduction length repeats a block; unused)
-    mac(1);
+  for (; kt + PG_NBUF <= KT; kt += PG_NBUF) {
+#pragma unroll
+    for (int p = 0; p < PG_NBUF; ++p) {
+      fetch(kt + p + PG_NBUF - 1, (p + PG_NBUF - 1) % PG_NBUF);
+      mac(p);
+    }
   }
-  if (kt < KT) mac(0);
+#pragma unroll
+  for (int p = 0; p < PG_NBUF - 1; ++p)
+    if (kt + p < KT) {
+      fetch(kt + p + PG_NBUF - 1, (p + PG_NBUF - 1) % PG_NBUF);
+      mac(p);
+    }
 
   // ---- epilogue: lane l holds outputs 4 (l / 16) .. + 3 of the tile for row l % 16 of the row tile
   const int c = lane >> 4, mi = lane & 15;
