@@ -104,25 +104,6 @@ typedef struct {
   uint64_t kv_bytes;          /* KV-cache bytes the launched attention kernels had to read */
 } ppd_stats;
 
-/* Kernel classes for ppd_get_kernel_time(). */
-enum {
-  PPD_KC_EMBED = 0,
-  PPD_KC_GEMM_QKV,   /* norm + Q,K,V projections */
-  PPD_KC_ATTN,       /* RoPE, KV write, attention over prefix + own position */
-  PPD_KC_ATTN_MERGE, /* merge of the position-chunk partials */
-  PPD_KC_GEMM_O,     /* output projection + residual */
-  PPD_KC_GEMM_FFN_IN,  /* norm + first FFN matrix (both matrices for SwiGLU) + activation */
-  PPD_KC_GEMM_FFN_OUT, /* second FFN matrix + residual */
-  PPD_KC_HEAD,       /* final norm + LM head */
-  PPD_KC_SELECT,     /* merge of the head's block top-k; early: candidates + their embedding rows;
-                        final: arg max, verification, adoption of the matching candidate
-                        (hidden row + KV tails -> cache) */
-  PPD_KC_COMMIT,     /* unused (adoption runs inside PPD_KC_SELECT) */
-  PPD_KC_PHASE,      /* not a kernel: one bracket around a whole phase of a round (groups = 1: the
-                        main token alone up to the exit layer; groups = 2: the d-dbar pipelined steps) */
-  PPD_KC_COUNT
-};
-
 /* Create a context.  Sec. 3 / Algorithm 2 inputs: d (dims->n_layers), dbar
  * (exit_layer, 1-based: the early prediction reads the output of that layer,
  * ceil(d/2) <= exit_layer <= d-1 as Theorem 4.1 requires dbar >= d/2), k.
@@ -194,42 +175,12 @@ int plain_greedy_step(ppd_ctx *ctx, int32_t *out_token);
  * for an unknown mode, top_k < 1 (mode 1), top_p outside (0, 1] (mode 2). */
 int ppd_set_sampling(ppd_ctx *ctx, int mode, int top_k, double top_p, uint64_t seed);
 
-/* Test hooks.  host_logits: HOST float[vocab].  Final-layer logits of the last
- * ppd_step / plain_greedy_step, and early-exit logits of the last ppd_step. */
-int ppd_get_logits(ppd_ctx *ctx, float *host_logits);
-int ppd_get_early_logits(ppd_ctx *ctx, float *host_logits);
-
 /* Copy the counters (HOST). */
 int ppd_get_stats(const ppd_ctx *ctx, ppd_stats *out);
 
-/* Timing with HIP events on the context's streams.  level 2: every launch is bracketed by two
- * events; level 1: only the phases of a round are (class PPD_KC_PHASE), so the kernels run
- * back to back as in normal operation; level 0: off.  While on, rounds are issued eagerly
- * instead of replayed from graphs.  ppd_get_kernel_time returns, for one class and one launch
- * shape (groups = 1: one row group; groups = 2: a two-group launch, or for PPD_KC_PHASE the
- * whole parallel phase), the summed elapsed milliseconds and the number of brackets since
- * profiling was switched on (HOST outputs).  Prefill is never profiled. */
-int ppd_set_profiling(ppd_ctx *ctx, int level);
 /* Rounds are replayed as captured HIP graphs (one per round shape) unless profiling is on;
  * on = 0 issues every launch eagerly instead.  Results are identical either way. */
 int ppd_set_graphs(ppd_ctx *ctx, int on);
-int ppd_get_kernel_time(ppd_ctx *ctx, int kernel_class, int groups, double *ms_total, uint64_t *launches);
-
-/* Measurement aid: launches the FFN-in GEMM (fused norm, first FFN matrix or the gate/up pair, activation)
- * reps times back to back between two HIP events on the context's stream, every launch on other layers' weights
- * than the one before, and reports the average milliseconds per launch (HOST output): the duration of the
- * kernel that bench.py prices against the HBM roofline, as it runs in a chain, without the event pair that
- * ppd_set_profiling(2) puts around every single launch.  groups = 2: the launch shape of a pipelined step (the
- * main row on one layer's matrices and the k candidate rows on another's: two weight streams per launch);
- * groups = 1: the main row alone (solo phase, plain steps).  Needs a prefilled context; overwrites the
- * activation rows, so the sequence state is gone afterwards (PPD_ESTATE until the next ppd_prefill). */
-int ppd_time_ffn_in(ppd_ctx *ctx, int reps, int groups, double *ms_per_launch);
-
-/* Measurement aid (not part of the method): read `bytes` of DEVICE memory at dev_buf `iters` times with a
- * kernel that does nothing but non-temporal 16-byte loads (a few launch shapes, the best counts), and report the rate in GB/s (HOST
- * output): the streaming rate this GPU reaches, next to which the decode kernels' rates are read.
- * bytes must be a positive multiple of 16; the buffer is only read.  Runs on its own stream, synchronous. */
-int ppd_stream_read_probe(const void *dev_buf, uint64_t bytes, int iters, double *gbps);
 
 /* The early prediction of Sec. 3 on its own, outside any context: logits = head . Norm(h) for one
  * intermediate hidden row (the LM classifier applied to the exit layer's state; Sec. 4.3: the final layer's

@@ -1,4 +1,4 @@
-"""ctypes binding of libppd (include/ppd.h): argument marshalling only.
+"""ctypes binding of libppd (include/ppd.h, include/ppd_measure.h): argument marshalling only.
 
 Every step of the decode path runs in the HIP kernels behind the C ABI; this
 module turns torch device tensors into the pointer tables the library takes

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libppd.so")
 PROBE_PATH = os.path.join(HERE, "ppd_pmc_probe")
 N_INST = 7
 DEPS = [os.path.join(CSRC, f) for f in ("ppd_engine.hip", "ppd_ops.hip", "ppd_pmc_probe.cpp", "ppd_prefill.hip", "ppd_prefill.h", "ppd_inst.hip", "ppd_kernels.h", "ppd_launch.h")] + \
-       [os.path.join(os.path.dirname(HERE), "include", "ppd.h")]
+       [os.path.join(os.path.dirname(HERE), "include", f) for f in ("ppd.h", "ppd_measure.h")]
 # -ffp-contract=off: every fused multiply-add in the kernels is an explicit fmaf, so a row's arithmetic
 # does not depend on which template instance it runs in.  Packed-fp32 code generation is switched off.
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",

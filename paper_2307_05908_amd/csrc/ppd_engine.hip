@@ -3,6 +3,7 @@
 // ppd_kernels.h; this file only decides which layers run on which rows.
 #define PPD_ENGINE_TU 1
 #include "../../include/ppd.h"
+#include "../../include/ppd_measure.h"
 #include "ppd_kernels.h"
 #include "ppd_launch.h"
 #include "ppd_prefill.h"

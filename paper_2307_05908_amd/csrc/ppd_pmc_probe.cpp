@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "../../include/ppd.h"
+#include "../../include/ppd_measure.h"
 
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fprintf(stderr, "HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); return 2; } } while (0)
 

@@ -1,4 +1,4 @@
-"""The C-ABI library without a GPU: it loads, exports what include/ppd.h declares,
+"""The C-ABI library without a GPU: it loads, exports what include/*.h declare,
 and rejects bad arguments before touching the device."""
 import ctypes
 import os
@@ -12,7 +12,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "ppd.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ppd_[a-z_]+|plain_greedy_step)\s*\(", text)))
 
