@@ -89,7 +89,7 @@ def fit_two_term(points):
     return float(t0), float(1.0 / slope / 1e3)
 
 
-def sweep_exit(args):
+def sweep(args):
     import numpy as np
     import torch
     import ppd_inputs as pi
@@ -97,17 +97,22 @@ def sweep_exit(args):
     rows = []
     base = pi.CONFIGS[args.config]
     d = base.n_layers
-    exits = [e for e in (d // 2, 5 * d // 8, 3 * d // 4, 7 * d // 8) if d // 2 <= e <= d - 1]
+    if args.sweep_k:     # the number of candidates at the middle exit layer
+        cases = [(k, args.exit_layer or d // 2) for k in (1, 3, 5)]
+        alphas = (1.0, 0.1, 0.02)
+    else:                # the exit layer at one k
+        cases = [(args.k or base.k, e) for e in (d // 2, 5 * d // 8, 3 * d // 4, 7 * d // 8) if d // 2 <= e <= d - 1]
+        alphas = (1.0, 0.1)
     K, W = args.steps, args.warmup
-    for alpha in (1.0, 0.1):
+    for alpha in alphas:
         # one model per alpha (the blocks after layer d/2 damped by alpha, as in the controlled-match-rate
         # configuration), every exit layer on that same model
         cfg = base.replace(alpha=alpha, seed_p=2005)
         model = pi.make_model(cfg)
         prompt = pi.make_prompt(cfg, args.prompt or cfg.n_prompt)
         dev = binding.upload_model(model, "cuda:0")
-        for e in exits:
-            P = binding.PPD(cfg, dev, k=args.k or cfg.k, exit_layer=e)
+        for k, e in cases:
+            P = binding.PPD(cfg, dev, k=k, exit_layer=e)
             P.ppd_prefill(prompt)
             for _ in range(W):
                 P.ppd_step(want_info=False)
@@ -125,17 +130,19 @@ def sweep_exit(args):
             for _ in range(K // 4):
                 P.plain_greedy_step()
             plain = (time.perf_counter() - t) / (K // 4)
-            rows.append({"alpha": alpha, "exit_layer": e, "p_correct": round(p_hat, 4),
+            rows.append({"alpha": alpha, "k": k, "exit_layer": e, "p_correct": round(p_hat, 4),
                          "main_layer_rows_per_token": round(main, 3),
                          "theorem_4_1_per_token": round((d * ell - (d - e) * ell * p_hat) / ell, 3),
+                         "layer_rows_per_token": round((st["main_layer_rows"] - st0["main_layer_rows"] +
+                                                        st["branch_layer_rows"] - st0["branch_layer_rows"]) / ell, 3),
                          "ms_per_round": round(wall / K * 1e3, 4), "plain_ms_per_token": round(plain * 1e3, 4)})
             print("sweep", rows[-1], file=sys.stderr, flush=True)
             P.close()
             del P
         del dev, model
         torch.cuda.empty_cache()
-    print(json.dumps({"metric": "exit-layer sweep, PPD decode on %s shape" % base.name, "n_gpus": 1, "steps": K,
-                      "warmup": W, "k": args.k or base.k, "data": "synthetic", "sweep": rows}))
+    print(json.dumps({"metric": "%s sweep, PPD decode on %s shape" % ("k" if args.sweep_k else "exit-layer", base.name),
+                      "n_gpus": 1, "steps": K, "warmup": W, "data": "synthetic", "sweep": rows}))
 
 
 def main():
@@ -153,6 +160,8 @@ def main():
     ap.add_argument("--profile-rounds", type=int, default=32)
     ap.add_argument("--sweep-exit", action="store_true",
                     help="sweep the exit layer (d/2 .. 7d/8) on the alpha = 1 and alpha = 0.1 models instead of the benchmark")
+    ap.add_argument("--sweep-k", action="store_true",
+                    help="instead of the benchmark line: k = 1, 3, 5 at the exit layer, on alpha = 1, 0.1 and 0.02 models")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -160,8 +169,8 @@ def main():
         print("bench.py: this build runs on one GPU only (the pipelined decode step of one sequence "
               "lives on one device); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
-    if args.sweep_exit:
-        sweep_exit(args)
+    if args.sweep_exit or args.sweep_k:
+        sweep(args)
         return
 
     import numpy as np
