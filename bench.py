@@ -75,7 +75,7 @@ def prefill_report(cfg, pi, rows, secs, first_secs):
         out["roofline"] = {"bound": "mfma", "achieved": round(2 * lin / secs / 1e12, 1), "peak": 2500.0, "unit": "TFLOP/s",
                            "frac": round(2 * lin / secs / 1e12 / 2500.0, 4),
                            "what": "bf16 MFMA work of the linear layers (two products per weight and row: rows = hi + lo) over the whole "
-                                   "prompt pass, attention (fp32 MFMA) and packing included in the time"}
+                                   "prompt pass, attention (the same MFMA, three products per operand pair) and packing included in the time"}
     return out
 
 

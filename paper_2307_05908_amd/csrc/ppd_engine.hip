@@ -75,6 +75,7 @@ struct ppd_ctx {
   uint16_t *pf_xp;       // packed two-term rows: the normalised hidden rows (input of the QKV and FFN-in GEMMs),
   uint16_t *pf_xa;       // the attention outputs (written by the attention kernel),
   uint16_t *pf_xf;       // the feed-forward activations (written by the FFN-in GEMM; zero beyond d_ff)
+  uint16_t *pf_qp, *pf_kp, *pf_vp;   // one layer's queries, keys, values as two-term operand blocks of the prompt attention
   int dev_pos_pending;   // host mirror of the device state's pending position (-1: unknown)
   float* xn;             // [rows][d_model] normalised rows of a prompt chunk (norm_rows_kernel)
   // sampling-based final prediction (Appendix B): 0 arg max, 1 top-k sampling, 2 top-p sampling
@@ -659,7 +660,7 @@ void account_round(ppd_ctx* c, int kind, int pos) {
 void free_all(ppd_ctx* c) {
   for (int i = 0; i < 4; ++i) if (c->graph[i]) (void)hipGraphExecDestroy(c->graph[i]);
   void* dev[] = {c->Kc, c->Vc, c->tailK, c->tailV, c->h, c->qkv, c->att, c->ffn, c->part, c->logits,
-                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->xn, c->pf_h, c->pf_qkv, c->pf_xp, c->pf_xa, c->pf_xf, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
+                 c->early_logits, c->early_spec, c->samp_w, c->samp_keys, c->xn, c->pf_h, c->pf_qkv, c->pf_xp, c->pf_xa, c->pf_xf, c->pf_qp, c->pf_kp, c->pf_vp, c->rope, c->ds, c->prompt_dev, c->pk_val, c->pk_idx};
   for (void* p : dev) (void)hipFree(p);
   for (void* p : c->owned) (void)hipFree(p);
   if (c->host_result) (void)hipHostFree(c->host_result);
@@ -676,15 +677,18 @@ int prefill_tiled(ppd_ctx* c, int rows) {
   const int dm = d.d_model, F = d.d_ff;
   const bool bias = d.has_bias != 0, swiglu = d.act == 2;
   if (rows > c->pf_rows) {
-    void* old[] = {c->pf_h, c->pf_qkv, c->pf_xp, c->pf_xa, c->pf_xf};
+    void* old[] = {c->pf_h, c->pf_qkv, c->pf_xp, c->pf_xa, c->pf_xf, c->pf_qp, c->pf_kp, c->pf_vp};
     for (void* p : old) (void)hipFree(p);
-    c->pf_h = c->pf_qkv = nullptr; c->pf_xp = c->pf_xa = c->pf_xf = nullptr; c->pf_rows = 0;
+    c->pf_h = c->pf_qkv = nullptr; c->pf_xp = c->pf_xa = c->pf_xf = nullptr; c->pf_qp = c->pf_kp = c->pf_vp = nullptr; c->pf_rows = 0;
     const size_t R = (size_t)((rows + 63) / 64) * 64;
     HIPCHK(c, hipMalloc((void**)&c->pf_h, R * dm * sizeof(float)));
     HIPCHK(c, hipMalloc((void**)&c->pf_qkv, R * 3 * dm * sizeof(float)));
     HIPCHK(c, hipMalloc((void**)&c->pf_xp, packed_bytes((int)R, dm)));
     HIPCHK(c, hipMalloc((void**)&c->pf_xa, packed_bytes((int)R, dm)));
     HIPCHK(c, hipMalloc((void**)&c->pf_xf, packed_bytes((int)R, F)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_qp, pattn_stage_bytes((int)R, d.n_heads, d.head_dim)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_kp, pattn_stage_bytes((int)R, d.n_heads, d.head_dim)));
+    HIPCHK(c, hipMalloc((void**)&c->pf_vp, pattn_stage_bytes((int)R, d.n_heads, d.head_dim)));
     c->pf_rows = (int)R;
   }
   // (the packed layouts depend on the row count: the padding columns of the activations are cleared per prompt)
@@ -726,9 +730,13 @@ int prefill_tiled(ppd_ctx* c, int rows) {
       kv.rope = d.pos == 1 ? c->rope : nullptr; kv.ds = c->ds; kv.HD = d.head_dim; kv.d_model = dm; kv.max_ctx = d.max_ctx;
       hipLaunchKernelGGL(chunk_kv_kernel, dim3(rows, d.n_heads), dim3(d.head_dim), 0, c->cur, kv);
       HIPCHK(c, hipGetLastError());
+      PKvPackArgs pk; memset(&pk, 0, sizeof pk);
+      pk.qkv = c->pf_qkv; pk.rope = kv.rope; pk.Qp = c->pf_qp; pk.Kp = c->pf_kp; pk.Vp = c->pf_vp;
+      pk.M = rows; pk.H = d.n_heads; pk.d_model = dm; pk.JP = (rows + 31) / 32; pk.scale = 1.44269504088896340736f / sqrtf((float)d.head_dim);
+      HIPCHK(c, launch_pkv_pack(c->cur, pk, d.head_dim));
       PAttnArgs pa; memset(&pa, 0, sizeof pa);
-      pa.qkv = c->pf_qkv; pa.Kc = kv.Kc; pa.Vc = kv.Vc; pa.rope = kv.rope; pa.ds = c->ds; pa.outp = c->pf_xa;
-      pa.M = rows; pa.H = d.n_heads; pa.d_model = dm; pa.max_ctx = d.max_ctx; pa.scale = 1.0f / sqrtf((float)d.head_dim);
+      pa.Qp = c->pf_qp; pa.Kp = c->pf_kp; pa.Vp = c->pf_vp; pa.outp = c->pf_xa;
+      pa.M = rows; pa.H = d.n_heads; pa.d_model = dm; pa.JP = pk.JP;
       HIPCHK(c, launch_pattn(c->cur, pa, d.head_dim));
     }
     HIPCHK(c, gemm(c->pf_xa, P.o, dm, dm, 0, 0, false, bias ? w.bo : nullptr, nullptr, nullptr, c->pf_h, c->pf_h, dm, 0));

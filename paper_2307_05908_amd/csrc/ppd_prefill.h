@@ -8,8 +8,10 @@
 //   pgemm_kernel        Y = epilogue(X W^T): register-tiled v_mfma_f32_16x16x32_bf16, weights in the repacked
 //                       1 KiB blocks of the decode path (A operand), packed rows as B operand, both straight from
 //                       memory (every wave-load is one contiguous kilobyte); products exact in fp32 as in decoding
-//   pattn_kernel        causal attention of all prompt rows over the fp32 key/value cache (blocks that are
-//                       v_mfma_f32_16x16x4_f32 operands), one wave per 16 query rows, running softmax
+//   pkv_pack_kernel     queries, keys, values of the prompt rows -> two-term operand blocks (the fp32 cache is filled
+//                       separately, by the decode path's own kernel)
+//   pattn_kernel        causal attention of all prompt rows on the same MFMA (three products per pair of two-term
+//                       operands), key/value steps staged through LDS for the four waves of a workgroup, running softmax
 //
 // Rounding order differs from the decode kernels (other tiles, other summation trees), so a cache filled here is
 // close to, not bit-identical with, one filled row by row; every decode step after it is the same arithmetic
@@ -26,6 +28,13 @@ constexpr int PG_TM = 4;            // 16-row tiles of the prompt per wave: 64 r
 #define PPD_PG_NBUF 4
 #endif
 constexpr int PG_NBUF = PPD_PG_NBUF;   // register buffers of operand blocks per wave
+#ifndef PPD_PG_GROUP_M
+#define PPD_PG_GROUP_M 8
+#endif
+#ifndef PPD_PG_GROUP_Q
+#define PPD_PG_GROUP_Q 8
+#endif
+constexpr int PG_GROUP_M = PPD_PG_GROUP_M, PG_GROUP_Q = PPD_PG_GROUP_Q;   // launch-order groups on one XCD (row blocks x output blocks)
 
 // ---- rows -> packed two-term operand blocks
 // Block (mt, kt) holds rows 16 mt .. +15, columns 32 kt .. +31 as 64 lanes x 8 bf16: lane i + 16 c = row i, columns
@@ -130,6 +139,7 @@ struct PGemmArgs {
   int ldy;
   int act;              // 0 none, 1 GELU, 2 ReLU (paired launches apply SwiGLU)
   int NB, MB;           // workgroup grid: NB blocks of 4 * TN tiles along the outputs, MB blocks of PG_TM tiles along the rows
+  int GQ, GM, MBG;      // launch order on one XCD: groups of GQ output blocks x GM row blocks, MBG = ceil(MB / GM) groups per output-block row
   // the outputs in packed two-term form instead of Y (they are the next GEMM's rows: the feed-forward activations):
   // [2][MT][KTp][64][8]; only outputs below ntot are written, the padding columns of the buffer stay as they are (zero)
   uint16_t* Yp; int KTp;
@@ -151,16 +161,20 @@ __device__ __forceinline__ void put_packed4(uint16_t* out, size_t plane_elems, i
 }
 
 
-// Workgroup b of the launch: an eighth of the output blocks per XCD (workgroups go round the XCDs in launch
-// order), and all row blocks of an output block one after the other on the same XCD, so that a weight block is
-// fetched from memory once and served to the other row blocks from that XCD's L2.
+// Workgroup b of the launch runs on XCD b % 8 (workgroups go round the XCDs in launch order), which owns every
+// eighth output block.  Its workgroups come in groups of GQ output blocks x GM row blocks, about what the XCD's
+// compute units work on at a time: the group reads GQ weight panels and GM row panels from memory once and serves
+// the other uses from that XCD's L2 (one output block against all row blocks would re-read every row panel for
+// every output block).  Measured on the 13B shape with 4095 rows: QKV projection 1.23 -> 1.06 ms.
 template <bool PAIRED, int TN>
 __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int b = blockIdx.x, xcd = b & 7, r = b >> 3;
-  const int nb = (r / a.MB) * 8 + xcd, mb = r - (r / a.MB) * a.MB;
-  if (nb >= a.NB) return;
+  const int per = a.GQ * a.GM, g = r / per, gi = r - g * per;
+  const int gq = g / a.MBG, gm = g - gq * a.MBG;
+  const int nb = (gq * a.GQ + gi / a.GM) * 8 + xcd, mb = gm * a.GM + gi % a.GM;
+  if (nb >= a.NB || mb >= a.MB) return;
   const int KT = a.KT;
   const int nt0 = (nb * PG_WAVES + wave) * TN, mt0 = mb * PG_TM;
   const size_t plane = (size_t)a.MT * KT * 1024;          // bytes per plane of the packed rows
@@ -291,125 +305,276 @@ __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
   }
 }
 
-// ---- causal attention over the cache
-// Row m of the prompt sits at position p0 + m and attends to cached positions [0, p0 + m]: the keys (rotated) and
-// values of all rows are in the cache before this kernel runs (chunk_kv_kernel).  A wave owns 16 consecutive rows
-// (the columns of its MFMAs) and walks the 16-position cache blocks up to its last row's position with a running
-// maximum and sum; a workgroup is 4 such waves of one head.
-struct PAttnArgs {
-  const float* qkv;     // [M][3 * d_model]: q | k | v as the projection left them (q not yet rotated)
-  const float* Kc; const float* Vc;   // this layer's cache
+// ---- causal attention of the prompt rows
+// Row m of the prompt sits at position m (the prompt pass starts from an empty cache) and attends to rows 0 .. m.
+// Queries (rotated, scaled), keys (rotated exactly as the cache holds them) and values are first put into two-term
+// bf16 operand blocks, so that scores and outputs run on v_mfma_f32_16x16x32_bf16 with the three products
+// hi.hi + hi.lo + lo.hi each (the lo.lo term is below 2^-16 of the result) instead of the fp32 MFMA, which
+// is a sixteenth as fast:
+//   Qp, Kp  [2][H][2 JP][HD / 32][64][8]   block (tile of 16 rows, 32 components): lane i + 16 c = row i, components 8 c .. + 7
+//   Vp      [2][H][JP][HD / 16][64][8]     block (32 rows, 16 components): lane i + 16 c = component i, and its 8 values
+//                                          are rows 4 c .. 4 c + 3 and 16 + 4 c .. 16 + 4 c + 3 of the 32
+// (JP = ceil(M / 32); rows past M are zeros.)  The odd row order of Vp is the one in which a lane holds its scores
+// after the two score MFMAs of a 32-row step: lane n + 16 c has, for query n, rows 4 c .. + 3 of either 16-row tile,
+// so the probabilities are the B operand of the output MFMA as they stand, without any exchange between lanes.
+struct PKvPackArgs {
+  const float* qkv;     // [M][3 * d_model]: q | k | v as the projection left them
   const float2* rope;   // [max_ctx][hd / 2] or null
-  const DevState* ds;   // row 0 sits at position ds->pos
-  uint16_t* outp;       // the outputs in packed two-term form [2][MT][d_model / 32][64][8] (rows of the output projection)
-  int M, H, d_model, max_ctx;
-  float scale;
+  uint16_t* Qp; uint16_t* Kp; uint16_t* Vp;
+  int M, H, d_model, JP;
+  float scale;          // factor on the queries: log2(e) / sqrt(hd), the softmax being evaluated as 2^(s - max)
 };
+struct PAttnArgs {
+  const uint16_t* Qp; const uint16_t* Kp; const uint16_t* Vp;
+  uint16_t* outp;       // the outputs in packed two-term form [2][MT][d_model / 32][64][8] (rows of the output projection)
+  int M, H, d_model, JP;
+};
+// bytes of each of Qp, Kp, Vp
+inline size_t pattn_stage_bytes(int M, int H, int HD) { return (size_t)2 * H * ((M + 31) / 32) * (HD / 16) * 1024; }
 
+#ifdef PPD_PREFILL_TU
+// One workgroup per (32 rows, head).
 template <int HD>
-__global__ __launch_bounds__(256) void pattn_kernel(PAttnArgs a) {
-  constexpr int NS = HD / 16, half = HD / 2;
+__global__ __launch_bounds__(256) void pkv_pack_kernel(PKvPackArgs a) {
+  constexpr int half = HD / 2, CB = HD / 32, CT = HD / 16, P8 = HD / 8;
+  const int jp = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+  const size_t plane = (size_t)a.H * a.JP * CT * 512;      // bf16 elements per plane (the same for all three)
+  // queries and keys: one 8-component piece of one row per item
+  for (int it = tid; it < 32 * P8; it += 256) {
+    const int rl = it / P8, c8 = it - rl * P8;             // row of the 32, piece
+    const int m = 32 * jp + rl, i0 = 8 * c8;
+    float q[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, k[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (m < a.M) {
+      const float* r = a.qkv + (size_t)m * 3 * a.d_model + (size_t)h * HD;
+      const float4 qa = *(const float4*)(r + i0), qb = *(const float4*)(r + i0 + 4);
+      const float4 ka = *(const float4*)(r + a.d_model + i0), kb = *(const float4*)(r + a.d_model + i0 + 4);
+      const float qv[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
+      const float kv[8] = {ka.x, ka.y, ka.z, ka.w, kb.x, kb.y, kb.z, kb.w};
+      if (a.rope) {
+        const int ip = i0 < half ? i0 + half : i0 - half;
+        const float4 qc = *(const float4*)(r + ip), qd = *(const float4*)(r + ip + 4);
+        const float4 kc = *(const float4*)(r + a.d_model + ip), kd = *(const float4*)(r + a.d_model + ip + 4);
+        const float qo[8] = {qc.x, qc.y, qc.z, qc.w, qd.x, qd.y, qd.z, qd.w};
+        const float ko[8] = {kc.x, kc.y, kc.z, kc.w, kd.x, kd.y, kd.z, kd.w};
+        const float2* cz = a.rope + (size_t)m * half + (i0 < half ? i0 : i0 - half);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const float2 w = cz[u];
+          if (i0 < half) { q[u] = fmaf(qv[u], w.x, -(qo[u] * w.y)); k[u] = fmaf(kv[u], w.x, -(ko[u] * w.y)); }
+          else           { q[u] = fmaf(qv[u], w.x, qo[u] * w.y);    k[u] = fmaf(kv[u], w.x, ko[u] * w.y); }
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { q[u] = qv[u]; k[u] = kv[u]; }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) q[u] *= a.scale;         // (scale carries log2(e): the attention kernel works with powers of two)
+    }
+    const size_t o = ((((size_t)h * 2 * a.JP + 2 * jp + (rl >> 4)) * CB + (c8 >> 2)) * 64 + (rl & 15) + 16 * (c8 & 3)) * 8;
+    uint4 hi, lo;
+    split2(q, hi, lo);
+    *(uint4*)(a.Qp + o) = hi; *(uint4*)(a.Qp + plane + o) = lo;
+    split2(k, hi, lo);
+    *(uint4*)(a.Kp + o) = hi; *(uint4*)(a.Kp + plane + o) = lo;
+  }
+  // values: one lane of one component tile per item
+  for (int it = tid; it < CT * 64; it += 256) {
+    const int ct = it >> 6, ln = it & 63, i = ln & 15, c = ln >> 4;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int m = 32 * jp + (e < 4 ? 4 * c + e : 16 + 4 * c + (e - 4));
+      v[e] = m < a.M ? a.qkv[(size_t)m * 3 * a.d_model + 2 * (size_t)a.d_model + (size_t)h * HD + 16 * ct + i] : 0.f;
+    }
+    const size_t o = ((((size_t)h * a.JP + jp) * CT + ct) * 64 + ln) * 8;
+    uint4 hi, lo;
+    split2(v, hi, lo);
+    *(uint4*)(a.Vp + o) = hi; *(uint4*)(a.Vp + plane + o) = lo;
+  }
+}
+
+// A workgroup is 4 waves of one head; a wave owns QT consecutive 16-row query tiles (the columns of its MFMAs),
+// the workgroup 64 QT consecutive rows.  The workgroup walks the 32-row steps of keys and values up to its last
+// row: a step's blocks (keys hi, lo; values hi, lo: 4 HD / 16 KiB) come into LDS by direct loads, a step ahead of
+// their use, two buffers; every wave reads them from there (a fourth of the traffic of four waves loading for
+// themselves) and keeps a running maximum and sum per row.
+template <int HD, int QT>
+__global__ __launch_bounds__(256, (QT <= 2 ? 2 : 1)) void pattn_kernel(PAttnArgs a) {
+  constexpr int CB = HD / 32, CT = HD / 16;
+  constexpr int STEP_BLKS = 4 * CB + 2 * CT;               // 1 KiB blocks per step: K hi (2 CB), K lo (2 CB), V hi (CT), V lo (CT)
+  extern __shared__ float4 pattn_lds4[];
+  char* const lds = (char*)pattn_lds4;                     // [2][STEP_BLKS] KiB
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int h = blockIdx.y;
-  const int qt = ((int)gridDim.x - 1 - (int)blockIdx.x) * 4 + wave;     // the longest rows first
-  if (qt * 16 >= a.M) return;
-  const int p0 = a.ds->pos;
+  const int wg = (int)gridDim.x - 1 - (int)blockIdx.x;     // the longest rows first
+  const int MT2 = 2 * a.JP;
+  const int qt0 = (wg * 4 + wave) * QT;                    // this wave's first tile (may lie past the prompt: then it only helps to load)
   const int bn = lane & 15, bc = lane >> 4;
-  const int mrow = qt * 16 + bn;                         // this lane's column: prompt row (may lie past M: computed, not stored)
-  const int mq = mrow < a.M ? mrow : a.M - 1;
-  const int pq = p0 + mq;                                // its position
-  // the row's query, rotated and scaled: components 16 s + 4 bc + u
-  f32x4 q4[NS];
-  {
-    const float* qr = a.qkv + (size_t)mq * 3 * a.d_model + (size_t)h * HD;
+  const size_t plane = (size_t)a.H * a.JP * CT * 1024;     // bytes per plane
+  u32x4 qh[QT][CB], ql[QT][CB];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const int i0 = 16 * s + 4 * bc;
-      const float4 v = *(const float4*)(qr + i0);
-      float x[4] = {v.x, v.y, v.z, v.w};
-      if (a.rope) {
-        const int ip = i0 < half ? i0 + half : i0 - half;
-        const float4 o = *(const float4*)(qr + ip);
-        const float xo[4] = {o.x, o.y, o.z, o.w};
-        const float2* cz = a.rope + (size_t)pq * half + (i0 < half ? i0 : i0 - half);
+  for (int t = 0; t < QT; ++t) {
+    const int tile = qt0 + t < MT2 ? qt0 + t : MT2 - 1;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const float2 t = cz[u];
-          x[u] = i0 < half ? fmaf(x[u], t.x, -(xo[u] * t.y)) : fmaf(x[u], t.x, xo[u] * t.y);
-        }
+    for (int cb = 0; cb < CB; ++cb) {
+      const char* src = (const char*)a.Qp + (((size_t)h * MT2 + tile) * CB + cb) * 1024 + lane * 16;
+      qh[t][cb] = *(const u32x4*)src;
+      ql[t][cb] = *(const u32x4*)(src + plane);
+    }
+  }
+  f32x4 oacc[QT][CT];
+  float mx[QT], l[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    mx[t] = -INFINITY; l[t] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) oacc[t][ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+  int wg_last = (wg * 4 + 3) * QT + QT - 1;
+  if (wg_last > MT2 - 1) wg_last = MT2 - 1;
+  const int nsteps = wg_last / 2 + 1;                      // steps the workgroup walks (<= JP)
+  auto stage = [&](int jp, int buf) {
+    for (int b = wave; b < STEP_BLKS; b += 4) {
+      const char* src;
+      if (b < 4 * CB) {
+        const int pl = b / (2 * CB), idx = b - pl * 2 * CB;
+        src = (const char*)a.Kp + pl * plane + (((size_t)h * MT2 + 2 * jp) * CB + idx) * 1024;
+      } else {
+        const int bb = b - 4 * CB, pl = bb / CT, idx = bb - pl * CT;
+        src = (const char*)a.Vp + pl * plane + (((size_t)h * a.JP + jp) * CT + idx) * 1024;
+      }
+      dma16(src + lane * 16, lds + ((size_t)buf * STEP_BLKS + b) * 1024);
+    }
+  };
+  stage(0, 0);
+  // the queries are waited for here, once: the compiler's own count of outstanding loads knows nothing of the
+  // direct-to-LDS requests, and a wait for a query register inside the loop would drain the step in flight
+#pragma unroll
+  for (int t = 0; t < QT; ++t)
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) asm volatile("" : "+v"(qh[t][cb]), "+v"(ql[t][cb]));
+  for (int jp = 0; jp < nsteps; ++jp) {
+    // this step's blocks have arrived (this wave's requests, then everybody's); everybody is done with the other buffer
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (jp + 1 < nsteps) stage(jp + 1, (jp + 1) & 1);
+    const char* const kb = lds + (size_t)(jp & 1) * STEP_BLKS * 1024 + lane * 16;
+    const char* const vb = kb + 4 * CB * 1024;
+    // the wave takes part while the step begins at or before the last row of its last tile; a tile that lies
+    // wholly before the step is computed all the same and masked (its weights come out as exact zeros)
+    if (2 * jp > qt0 + QT - 1) continue;
+    f32x4 s[QT][2];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) { s[t][0] = (f32x4){0.f, 0.f, 0.f, 0.f}; s[t][1] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+    // (consecutive MFMAs go to different accumulators: none waits for the one before it)
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+      bf16x8 kh[2], kl[2];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        kh[x] = __builtin_bit_cast(bf16x8, *(const u32x4*)(kb + (x * CB + cb) * 1024));
+        kl[x] = __builtin_bit_cast(bf16x8, *(const u32x4*)(kb + ((2 + x) * CB + cb) * 1024));
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) q4[s][u] = x[u] * a.scale;
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int t = 0; t < QT; ++t) s[t][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kh[x], __builtin_bit_cast(bf16x8, qh[t][cb]), s[t][x], 0, 0, 0);
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int t = 0; t < QT; ++t) s[t][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kl[x], __builtin_bit_cast(bf16x8, qh[t][cb]), s[t][x], 0, 0, 0);
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int t = 0; t < QT; ++t) s[t][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kh[x], __builtin_bit_cast(bf16x8, ql[t][cb]), s[t][x], 0, 0, 0);
+    }
+    // s[t][x][r]: row 32 jp + 16 x + 4 bc + r against query row 16 (qt0 + t) + bn
+    const bool diag = 32 * jp + 31 > 16 * qt0;             // the step reaches past the first row of the wave's first tile
+    u32x4 ph[QT], plo[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      const int qrow = 16 * (qt0 + t) + bn;
+      float sv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sv[e] = s[t][e >> 2][e & 3];
+      if (diag) {                                          // mask what lies after each row
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (32 * jp + 16 * (e >> 2) + 4 * bc + (e & 3) > qrow) sv[e] = -INFINITY;
+      }
+      float bm = sv[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) bm = fmaxf(bm, sv[e]);
+      // the running maximum of a query is the same in its four lanes; it moves only when some lane of the wave has
+      // met a larger score (rare after the first steps), and only then are the lanes compared and the sums rescaled
+      if (__any(bm > mx[t])) {
+        bm = fmaxf(bm, __shfl_xor(bm, 16, WAVE));
+        bm = fmaxf(bm, __shfl_xor(bm, 32, WAVE));
+        const float mnew = fmaxf(mx[t], bm);               // finite from the first step on: row 0 is visible to every query
+        const float resc = __builtin_amdgcn_exp2f(mx[t] - mnew);
+        mx[t] = mnew;
+        l[t] *= resc;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) oacc[t][ct][r] *= resc;
+      }
+      float pv[8], ps = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { pv[e] = __builtin_amdgcn_exp2f(sv[e] - mx[t]); ps += pv[e]; }
+      l[t] += ps;                                          // this lane's 8 rows of the step; the four lanes of a query are added at the end
+      uint4 hi, lo;
+      split2(pv, hi, lo);
+      ph[t] = (u32x4){hi.x, hi.y, hi.z, hi.w}; plo[t] = (u32x4){lo.x, lo.y, lo.z, lo.w};
+    }
+    // outputs: rows = components 16 ct + 4 bc + r, reduction over the step's 32 rows in the order Vp holds them
+#pragma unroll
+    for (int c2 = 0; c2 < CT; c2 += 2) {
+      bf16x8 vh[2], vl[2];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        vh[x] = __builtin_bit_cast(bf16x8, *(const u32x4*)(vb + (c2 + x) * 1024));
+        vl[x] = __builtin_bit_cast(bf16x8, *(const u32x4*)(vb + (CT + c2 + x) * 1024));
+      }
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int t = 0; t < QT; ++t) oacc[t][c2 + x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh[x], __builtin_bit_cast(bf16x8, ph[t]), oacc[t][c2 + x], 0, 0, 0);
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int t = 0; t < QT; ++t) oacc[t][c2 + x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl[x], __builtin_bit_cast(bf16x8, ph[t]), oacc[t][c2 + x], 0, 0, 0);
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int t = 0; t < QT; ++t) oacc[t][c2 + x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh[x], __builtin_bit_cast(bf16x8, plo[t]), oacc[t][c2 + x], 0, 0, 0);
     }
   }
-  const int plast = p0 + (qt * 16 + 15 < a.M ? qt * 16 + 15 : a.M - 1);      // last position any column of this wave sees
-  const int nblk = plast / KV_BLOCK + 1;
-  const size_t hb = (size_t)h * kv_blocks(a.max_ctx);
-  const char* kb = (const char*)a.Kc + hb * (NS * 1024) + lane * 16;
-  const char* vb = (const char*)a.Vc + hb * (NS * 1024) + lane * 16;
-  f32x4 kreg[NS], vreg[NS], oacc[NS];
+  const int MT = (a.M + 15) / 16, KT = a.d_model / 32;
 #pragma unroll
-  for (int s = 0; s < NS; ++s) oacc[s] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float mx = -INFINITY, l = 0.f;
-#pragma unroll
-  for (int s = 0; s < NS; ++s) kreg[s] = *(const f32x4*)(kb + s * 1024);
-#pragma unroll
-  for (int s = 0; s < NS; ++s) vreg[s] = *(const f32x4*)(vb + s * 1024);
-  for (int jb = 0; jb < nblk; ++jb) {
-    // scores of the block's 16 positions for the wave's 16 rows: sacc[jj] = position 16 jb + 4 bc + jj, row bn
-    f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-      for (int u = 0; u < 4; ++u) sacc = __builtin_amdgcn_mfma_f32_16x16x4f32(kreg[s][u], q4[s][u], sacc, 0, 0, 0);
-    const int jn = jb + 1 < nblk ? jb + 1 : jb;          // next block's keys (the last iteration repeats its own: unused)
-#pragma unroll
-    for (int s = 0; s < NS; ++s) kreg[s] = *(const f32x4*)(kb + ((size_t)jn * NS + s) * 1024);
-    float bm = -INFINITY;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const int j = jb * KV_BLOCK + 4 * bc + jj;
-      if (j > pq) sacc[jj] = -INFINITY;
-      bm = fmaxf(bm, sacc[jj]);
+  for (int t = 0; t < QT; ++t) {
+    const int mrow = 16 * (qt0 + t) + bn;
+    float lt = l[t];                                       // lanes bc = 0, 1, 2, 3 of the query, in that order
+    {
+      const float l1 = __shfl(lt, bn + 16, WAVE), l2 = __shfl(lt, bn + 32, WAVE), l3 = __shfl(lt, bn + 48, WAVE);
+      lt = ((__shfl(lt, bn, WAVE) + l1) + l2) + l3;
     }
-    bm = fmaxf(bm, __shfl_xor(bm, 16, WAVE));
-    bm = fmaxf(bm, __shfl_xor(bm, 32, WAVE));
-    const float mnew = fmaxf(mx, bm);                    // finite from the first block on: position 0 is visible to every row
-    const float resc = expf(mx - mnew);
-    f32x4 p4;
-    float ps = 0.f;
+    if (mrow >= a.M) continue;
+    const float inv = 1.0f / lt;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) { p4[jj] = expf(sacc[jj] - mnew); ps += p4[jj]; }
-    ps += __shfl_xor(ps, 16, WAVE);
-    ps += __shfl_xor(ps, 32, WAVE);
-    l = fmaf(l, resc, ps);
-    mx = mnew;
-    // outputs: rows = components 16 s + 4 bc + jj, reduction over the block's positions 4 bc + u (p4 is the B operand as it stands)
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) oacc[s][jj] *= resc;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) oacc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(vreg[s][u], p4[u], oacc[s], 0, 0, 0);
-    }
-#pragma unroll
-    for (int s = 0; s < NS; ++s) vreg[s] = *(const f32x4*)(vb + ((size_t)jn * NS + s) * 1024);
-  }
-  if (mrow < a.M) {
-    const float inv = 1.0f / l;
-    const int MT = (a.M + 15) / 16, KT = a.d_model / 32;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const float y[4] = {oacc[s][0] * inv, oacc[s][1] * inv, oacc[s][2] * inv, oacc[s][3] * inv};
-      put_packed4(a.outp, (size_t)MT * KT * 512, KT, mrow, h * HD + 16 * s + 4 * bc, y);
+    for (int ct = 0; ct < CT; ++ct) {
+      const float y[4] = {oacc[t][ct][0] * inv, oacc[t][ct][1] * inv, oacc[t][ct][2] * inv, oacc[t][ct][3] * inv};
+      put_packed4(a.outp, (size_t)MT * KT * 512, KT, mrow, h * HD + 16 * ct + 4 * bc, y);
     }
   }
 }
+#endif
 
 // launchers (ppd_prefill.hip)
 hipError_t launch_pack_rows(hipStream_t stream, const PackArgs& a);
 hipError_t launch_pgemm(hipStream_t stream, PGemmArgs a, bool paired);
+hipError_t launch_pkv_pack(hipStream_t stream, const PKvPackArgs& a, int head_dim);
 hipError_t launch_pattn(hipStream_t stream, const PAttnArgs& a, int head_dim);
 // bytes of the packed form of M rows of K columns
 inline size_t packed_bytes(int M, int K) { return (size_t)2 * ((M + 15) / 16) * ((K + 31) / 32) * 1024; }

@@ -2,6 +2,10 @@
 #define PPD_PREFILL_TU 1
 #include "ppd_prefill.h"
 
+#ifndef PPD_PATTN_QT
+#define PPD_PATTN_QT 0   // 1, 2, 4: force the query tiles per wave (measurement builds)
+#endif
+
 namespace ppd {
 
 hipError_t launch_pack_rows(hipStream_t stream, const PackArgs& a) {
@@ -17,7 +21,11 @@ hipError_t launch_pgemm(hipStream_t stream, PGemmArgs a, bool paired) {
   const int tn = ((a.NT + PG_WAVES * 4 - 1) / (PG_WAVES * 4)) * mb >= 384 ? 4 : 2;
   a.MB = mb;
   a.NB = (a.NT + PG_WAVES * tn - 1) / (PG_WAVES * tn);
-  const dim3 grid(8 * ((a.NB + 7) / 8) * a.MB);
+  a.GM = mb < PG_GROUP_M ? mb : PG_GROUP_M;
+  a.GQ = PG_GROUP_Q;
+  a.MBG = (mb + a.GM - 1) / a.GM;
+  const int nbq = (a.NB + 7) / 8;
+  const dim3 grid(8 * ((nbq + a.GQ - 1) / a.GQ) * a.GQ * a.MBG * a.GM);
   if (paired) {
     if (tn == 4) hipLaunchKernelGGL((pgemm_kernel<true, 4>), grid, dim3(PG_THREADS), 0, stream, a);
     else hipLaunchKernelGGL((pgemm_kernel<true, 2>), grid, dim3(PG_THREADS), 0, stream, a);
@@ -28,12 +36,29 @@ hipError_t launch_pgemm(hipStream_t stream, PGemmArgs a, bool paired) {
   return hipGetLastError();
 }
 
-hipError_t launch_pattn(hipStream_t stream, const PAttnArgs& a, int head_dim) {
-  if (a.M < 1 || (head_dim != 64 && head_dim != 128)) return hipErrorInvalidValue;
-  const dim3 grid((a.M + 63) / 64, a.H);
-  if (head_dim == 128) hipLaunchKernelGGL(pattn_kernel<128>, grid, dim3(256), 0, stream, a);
-  else hipLaunchKernelGGL(pattn_kernel<64>, grid, dim3(256), 0, stream, a);
+hipError_t launch_pkv_pack(hipStream_t stream, const PKvPackArgs& a, int head_dim) {
+  if (a.M < 1 || a.JP != (a.M + 31) / 32 || (head_dim != 64 && head_dim != 128) || (a.d_model & 3)) return hipErrorInvalidValue;
+  const dim3 grid(a.JP, a.H);
+  if (head_dim == 128) hipLaunchKernelGGL(pkv_pack_kernel<128>, grid, dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(pkv_pack_kernel<64>, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
+}
+
+template <int HD, int QT>
+static hipError_t launch_pattn_t(hipStream_t stream, const PAttnArgs& a) {
+  const int MT = (a.M + 15) / 16;
+  const dim3 grid((MT + 4 * QT - 1) / (4 * QT), a.H);
+  const size_t lds = (size_t)2 * (4 * (HD / 32) + 2 * (HD / 16)) * 1024;
+  hipLaunchKernelGGL((pattn_kernel<HD, QT>), grid, dim3(256), lds, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_pattn(hipStream_t stream, const PAttnArgs& a, int head_dim) {
+  if (a.M < 1 || a.JP != (a.M + 31) / 32 || (head_dim != 64 && head_dim != 128) || a.d_model % 32) return hipErrorInvalidValue;
+  // rows per workgroup (64 QT): more for long prompts, whose workgroups are plenty
+  const int qt = PPD_PATTN_QT ? PPD_PATTN_QT : (a.M >= 2048 ? 4 : (a.M >= 1024 ? 2 : 1));
+  if (head_dim == 128) return qt == 4 ? launch_pattn_t<128, 4>(stream, a) : (qt == 2 ? launch_pattn_t<128, 2>(stream, a) : launch_pattn_t<128, 1>(stream, a));
+  return qt == 4 ? launch_pattn_t<64, 4>(stream, a) : (qt == 2 ? launch_pattn_t<64, 2>(stream, a) : launch_pattn_t<64, 1>(stream, a));
 }
 
 }  // namespace ppd
