@@ -725,14 +725,10 @@ int prefill_tiled(ppd_ctx* c, int rows) {
     HIPCHK(c, gemm(c->pf_xp, P.qkv, dm, dm, dm, dm, false, bias ? w.bq : nullptr, bias ? w.bk : nullptr, bias ? w.bv : nullptr,
                    nullptr, c->pf_qkv, 3 * dm, 0));
     {
-      ChunkKvArgs kv; memset(&kv, 0, sizeof kv);
-      kv.qkv = c->pf_qkv; kv.Kc = (float*)(c->Kc + (size_t)l * cache_layer_bytes(c)); kv.Vc = (float*)(c->Vc + (size_t)l * cache_layer_bytes(c));
-      kv.rope = d.pos == 1 ? c->rope : nullptr; kv.ds = c->ds; kv.HD = d.head_dim; kv.d_model = dm; kv.max_ctx = d.max_ctx;
-      hipLaunchKernelGGL(chunk_kv_kernel, dim3(rows, d.n_heads), dim3(d.head_dim), 0, c->cur, kv);
-      HIPCHK(c, hipGetLastError());
       PKvPackArgs pk; memset(&pk, 0, sizeof pk);
-      pk.qkv = c->pf_qkv; pk.rope = kv.rope; pk.Qp = c->pf_qp; pk.Kp = c->pf_kp; pk.Vp = c->pf_vp;
-      pk.M = rows; pk.H = d.n_heads; pk.d_model = dm; pk.JP = (rows + 31) / 32; pk.scale = 1.44269504088896340736f / sqrtf((float)d.head_dim);
+      pk.qkv = c->pf_qkv; pk.rope = d.pos == 1 ? c->rope : nullptr; pk.Qp = c->pf_qp; pk.Kp = c->pf_kp; pk.Vp = c->pf_vp;
+      pk.Kc = (float*)(c->Kc + (size_t)l * cache_layer_bytes(c)); pk.Vc = (float*)(c->Vc + (size_t)l * cache_layer_bytes(c));
+      pk.max_ctx = d.max_ctx; pk.M = rows; pk.H = d.n_heads; pk.d_model = dm; pk.JP = (rows + 31) / 32; pk.scale = 1.44269504088896340736f / sqrtf((float)d.head_dim);
       HIPCHK(c, launch_pkv_pack(c->cur, pk, d.head_dim));
       PAttnArgs pa; memset(&pa, 0, sizeof pa);
       pa.Qp = c->pf_qp; pa.Kp = c->pf_kp; pa.Vp = c->pf_vp; pa.outp = c->pf_xa;

@@ -5,11 +5,11 @@
 // handful of rows and the wrong one for a prompt: here the prompt's rows are a real matrix operand.
 //
 //   pack_rows_kernel    rows (after an optional norm) -> two bf16 terms x = hi + lo in MFMA operand blocks
-//   pgemm_kernel        Y = epilogue(X W^T): register-tiled v_mfma_f32_16x16x32_bf16, weights in the repacked
+//   pgemm_kernel        Y = epilogue(X W^T): register-tiled v_mfma_f32_32x32x16_bf16, weights in the repacked
 //                       1 KiB blocks of the decode path (A operand), packed rows as B operand, both straight from
 //                       memory (every wave-load is one contiguous kilobyte); products exact in fp32 as in decoding
-//   pkv_pack_kernel     queries, keys, values of the prompt rows -> two-term operand blocks (the fp32 cache is filled
-//                       separately, by the decode path's own kernel)
+//   pkv_pack_kernel     queries, keys, values of the prompt rows -> two-term operand blocks, and keys and values into
+//                       the fp32 cache in the decode path's layout
 //   pattn_kernel        causal attention of all prompt rows on the same MFMA (three products per pair of two-term
 //                       operands), key/value steps staged through LDS for the four waves of a workgroup, running softmax
 //
@@ -21,11 +21,14 @@
 
 namespace ppd {
 
-constexpr int PG_THREADS = 256;     // 4 waves
-constexpr int PG_WAVES = PG_THREADS / WAVE;
-constexpr int PG_TM = 4;            // 16-row tiles of the prompt per wave: 64 rows per workgroup
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int PG_WAVES = 4;                        // waves that multiply: each its own outputs against the workgroup's prompt rows
+constexpr int PG_THREADS = (PG_WAVES + 1) * WAVE;  // and one wave that stages the rows in LDS for them
+constexpr int PG_D = 2, PG_R = PG_D + 2;           // stages of rows in flight ahead of their use; ring slots in LDS
+constexpr int PG_STAGE_BLKS = 16;                  // 1 KiB blocks per stage: KB 32-column blocks x 2 planes x TMB 16-row blocks
 #ifndef PPD_PG_NBUF
-#define PPD_PG_NBUF 4
+#define PPD_PG_NBUF 6
 #endif
 constexpr int PG_NBUF = PPD_PG_NBUF;   // register buffers of operand blocks per wave
 #ifndef PPD_PG_GROUP_M
@@ -138,7 +141,7 @@ struct PGemmArgs {
   int N[3], ntot;       // rows per segment (bias lookup); logical output rows
   int ldy;
   int act;              // 0 none, 1 GELU, 2 ReLU (paired launches apply SwiGLU)
-  int NB, MB;           // workgroup grid: NB blocks of 4 * TN tiles along the outputs, MB blocks of PG_TM tiles along the rows
+  int NB, MB;           // workgroup grid: NB blocks of 4 * TN 16-row blocks along the outputs, MB blocks of TMB 16-row blocks along the rows
   int GQ, GM, MBG;      // launch order on one XCD: groups of GQ output blocks x GM row blocks, MBG = ceil(MB / GM) groups per output-block row
   // the outputs in packed two-term form instead of Y (they are the next GEMM's rows: the feed-forward activations):
   // [2][MT][KTp][64][8]; only outputs below ntot are written, the padding columns of the buffer stay as they are (zero)
@@ -166,8 +169,24 @@ __device__ __forceinline__ void put_packed4(uint16_t* out, size_t plane_elems, i
 // compute units work on at a time: the group reads GQ weight panels and GM row panels from memory once and serves
 // the other uses from that XCD's L2 (one output block against all row blocks would re-read every row panel for
 // every output block).  Measured on the 13B shape with 4095 rows: QKV projection 1.23 -> 1.06 ms.
-template <bool PAIRED, int TN>
+// The MFMA is v_mfma_f32_32x32x16_bf16 (a 16x16x32 one issues at half its rate on this part).  Its operands
+// come out of the 16-row blocks as they lie in memory: lane r + 32 h of a 32-row tile reads 16 bytes of the
+// 16-row block r / 16 at lane position (r % 16) + 16 (2 w + h), w = 0, 1 being the two 16-column halves of the
+// 32-column block, so one block pair feeds two MFMAs per operand pair, and weights and rows pair up column by
+// column whatever order the hardware takes the 16 columns in.
+// A workgroup is four multiplying waves and one staging wave.  Multiplying wave w holds TN / 2 x TMB / 2
+// accumulator tiles of 32 x 32: its own TN 16-row weight blocks, straight from memory into PG_NBUF register
+// buffers, against the workgroup's 16 TMB prompt rows, which the staging wave brings into LDS by direct loads (a
+// ring of PG_R stages, PG_D in flight; one barrier per stage hands a stage over): a row block is fetched once per
+// workgroup instead of once per wave, and the waits on the two kinds of loads do not mix in one wave's counter.
+template <bool PAIRED, int TN, int TMB>
 __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
+  constexpr int TW = TN / 2, TX = TMB / 2;                 // 32-row tiles per wave: weights, prompt rows
+  constexpr int KB = PG_STAGE_BLKS / (2 * TMB);            // 32-column blocks per stage
+  static_assert(TN % 2 == 0 && TMB % 2 == 0 && KB >= 1 && KB * 2 * TMB == PG_STAGE_BLKS && PG_NBUF % KB == 0, "tile shapes");
+  static_assert(PG_D * PG_STAGE_BLKS < 64, "the staging wave's wait counts its requests in flight");
+  extern __shared__ float4 pg_lds4[];
+  char* const lds = (char*)pg_lds4;                        // [PG_R][PG_STAGE_BLKS] KiB
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int b = blockIdx.x, xcd = b & 7, r = b >> 3;
@@ -176,45 +195,95 @@ __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
   const int nb = (gq * a.GQ + gi / a.GM) * 8 + xcd, mb = gm * a.GM + gi % a.GM;
   if (nb >= a.NB || mb >= a.MB) return;
   const int KT = a.KT;
-  const int nt0 = (nb * PG_WAVES + wave) * TN, mt0 = mb * PG_TM;
+  const int mt0 = mb * TMB;                                // in 16-row blocks
   const size_t plane = (size_t)a.MT * KT * 1024;          // bytes per plane of the packed rows
-  const char* wbase[TN]; const char* xbase[PG_TM];
+  const int nstg = (KT + KB - 1) / KB;
+
+  if (wave == PG_WAVES) {
+    // ---- the staging wave: stage s = 32-column blocks KB s .. KB s + KB - 1 of the workgroup's rows, both planes
+    const char* const src0 = (const char*)a.Xp + lane * 16;
+    auto stage = [&](int s) {
+      char* const dst = lds + (size_t)(s % PG_R) * PG_STAGE_BLKS * 1024;
 #pragma unroll
-  for (int t = 0; t < TN; ++t) {
-    const int nt = nt0 + t < a.NT ? nt0 + t : a.NT - 1;   // (tiles past the matrix re-read its last tile; never stored)
-    wbase[t] = (const char*)a.P + (size_t)nt * KT * 1024 + lane * 16;
+      for (int kk = 0; kk < KB; ++kk) {
+        const int kt = KB * s + kk < KT ? KB * s + kk : KT - 1;    // (a block past the end repeats the last one; unused)
+#pragma unroll
+        for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+          for (int tb = 0; tb < TMB; ++tb) {
+            const int mt = mt0 + tb < a.MT ? mt0 + tb : a.MT - 1;  // (blocks past the prompt re-read its last block; never stored)
+            dma16(src0 + pl * plane + ((size_t)mt * KT + kt) * 1024, dst + ((kk * 2 + pl) * TMB + tb) * 1024);
+          }
+      }
+    };
+    for (int s = 0; s < PG_D && s < nstg; ++s) stage(s);
+    for (int s = 0; s < nstg; ++s) {
+      // slot (s + PG_D) % PG_R was last read for stage s - 2: every wave is past that (it has met barrier s - 1)
+      if (s + PG_D < nstg) {
+        stage(s + PG_D);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PG_D * PG_STAGE_BLKS) : "memory");   // all but the PG_D youngest stages: stage s is in
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+      __syncthreads();
+    }
+    return;
   }
+
+  // ---- the multiplying waves
+  const int nt0 = (nb * PG_WAVES + wave) * TN;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int lane_off = ((lr & 15) + 16 * lh) * 16;         // + 512 for the second 16-column half
+  const char* wbase[TW];
 #pragma unroll
-  for (int t = 0; t < PG_TM; ++t) {
-    const int mt = mt0 + t < a.MT ? mt0 + t : a.MT - 1;
-    xbase[t] = (const char*)a.Xp + (size_t)mt * KT * 1024 + lane * 16;
+  for (int t = 0; t < TW; ++t) {
+    int nt = nt0 + 2 * t + (lr >> 4);
+    if (nt >= a.NT) nt = a.NT - 1;                         // (blocks past the matrix re-read its last block; never stored)
+    wbase[t] = (const char*)a.P + (size_t)nt * KT * 1024 + lane_off;
   }
-  f32x4 acc[TN][PG_TM];
+  const char* const xlds = lds + (lr >> 4) * 1024 + lane_off;
+  f32x16 acc[TW][TX];
 #pragma unroll
-  for (int i = 0; i < TN; ++i)
+  for (int i = 0; i < TW; ++i)
 #pragma unroll
-    for (int j = 0; j < PG_TM; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  // PG_NBUF register buffers: the blocks of the next PG_NBUF - 1 reduction steps are in flight while one is multiplied
-  u32x4 wa[PG_NBUF][TN], xh[PG_NBUF][PG_TM], xl[PG_NBUF][PG_TM];
+    for (int j = 0; j < TX; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  // PG_NBUF register buffers of weight blocks: those of the next PG_NBUF - 1 reduction steps are in flight while one is multiplied
+  u32x4 wa[PG_NBUF][TW][2];
   auto fetch = [&](int kt, int buf) {
     const size_t o = (size_t)(kt < KT ? kt : KT - 1) * 1024;       // (requests past the end repeat the last block; unused)
 #pragma unroll
-    for (int t = 0; t < TN; ++t) wa[buf][t] = *(const u32x4*)(wbase[t] + o);
+    for (int t = 0; t < TW; ++t)
 #pragma unroll
-    for (int t = 0; t < PG_TM; ++t) { xh[buf][t] = *(const u32x4*)(xbase[t] + o); xl[buf][t] = *(const u32x4*)(xbase[t] + plane + o); }
+      for (int w = 0; w < 2; ++w) wa[buf][t][w] = *(const u32x4*)(wbase[t] + o + 512 * w);
   };
-  // (all products with the first terms, then all with the second: no MFMA waits for the one before it)
-  auto mac = [&](int buf) {
+  // one 32-column block: the rows' two terms from LDS (all products with the first terms, then all with the second:
+  // no MFMA waits for the one before it)
+  auto mac = [&](int buf, int kt, int kk) {
+    const char* const xs = xlds + ((size_t)((kt / KB) % PG_R) * PG_STAGE_BLKS + kk * 2 * TMB) * 1024;
+    u32x4 xh[TX][2], xl[TX][2];
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+    for (int j = 0; j < TX; ++j)
 #pragma unroll
-      for (int j = 0; j < PG_TM; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wa[buf][i]), __builtin_bit_cast(bf16x8, xh[buf][j]), acc[i][j], 0, 0, 0);
+      for (int w = 0; w < 2; ++w) {
+        xh[j][w] = *(const u32x4*)(xs + (2 * j) * 1024 + 512 * w);
+        xl[j][w] = *(const u32x4*)(xs + (TMB + 2 * j) * 1024 + 512 * w);
+      }
 #pragma unroll
-    for (int i = 0; i < TN; ++i)
+    for (int w = 0; w < 2; ++w)
 #pragma unroll
-      for (int j = 0; j < PG_TM; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wa[buf][i]), __builtin_bit_cast(bf16x8, xl[buf][j]), acc[i][j], 0, 0, 0);
+      for (int i = 0; i < TW; ++i)
+#pragma unroll
+        for (int j = 0; j < TX; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa[buf][i][w]), __builtin_bit_cast(bf16x8, xh[j][w]), acc[i][j], 0, 0, 0);
+#pragma unroll
+    for (int w = 0; w < 2; ++w)
+#pragma unroll
+      for (int i = 0; i < TW; ++i)
+#pragma unroll
+        for (int j = 0; j < TX; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa[buf][i][w]), __builtin_bit_cast(bf16x8, xl[j][w]), acc[i][j], 0, 0, 0);
   };
 #pragma unroll
   for (int p = 0; p < PG_NBUF - 1; ++p) fetch(p, p);
@@ -222,84 +291,77 @@ __global__ __launch_bounds__(PG_THREADS) void pgemm_kernel(PGemmArgs a) {
   for (; kt + PG_NBUF <= KT; kt += PG_NBUF) {
 #pragma unroll
     for (int p = 0; p < PG_NBUF; ++p) {
+      if (p % KB == 0) __syncthreads();                    // the stage of this block is in LDS
       fetch(kt + p + PG_NBUF - 1, (p + PG_NBUF - 1) % PG_NBUF);
-      mac(p);
+      mac(p, kt + p, p % KB);
     }
   }
 #pragma unroll
   for (int p = 0; p < PG_NBUF - 1; ++p)
     if (kt + p < KT) {
+      if (p % KB == 0) __syncthreads();
       fetch(kt + p + PG_NBUF - 1, (p + PG_NBUF - 1) % PG_NBUF);
-      mac(p);
+      mac(p, kt + p, p % KB);
     }
 
-  // ---- epilogue: lane l holds outputs 4 (l / 16) .. + 3 of the tile for row l % 16 of the row tile
-  const int c = lane >> 4, mi = lane & 15;
+  // ---- epilogue: registers 4 q .. 4 q + 3 of a tile are its rows 8 q + 4 (l / 32) .. + 3 (weight rows) for column l % 32
+  // (prompt row)
   const uint16_t* const B0 = (const uint16_t*)a.B[0];
   const uint16_t* const B1 = (const uint16_t*)a.B[1];
   const uint16_t* const B2 = (const uint16_t*)a.B[2];
 #pragma unroll
-  for (int i = 0; i < TN; ++i) {
-    const int nt = nt0 + i;
-    if (nt >= a.NT) continue;
+  for (int i = 0; i < TW; ++i) {
 #pragma unroll
-    for (int j = 0; j < PG_TM; ++j) {
-      const int m = (mt0 + j) * 16 + mi;
-      f32x4 v = acc[i][j];
+    for (int j = 0; j < TX; ++j) {
+      const int m = (mt0 + 2 * j) * 16 + lr;
+      if (m >= a.M) continue;
       if (PAIRED) {
-        // the tile's rows 0..7 are gate rows, 8..15 the up rows of the same 8 outputs: lanes c = 0, 1 take the
-        // up values of lanes c + 2
-        f32x4 u;
+        // a 16-row block holds the gate rows (0..7) and the up rows (8..15) of 8 outputs: register groups 0, 1 are
+        // gate and up of the first block's outputs 4 (l / 32) .. + 3, groups 2, 3 of the second block's
 #pragma unroll
-        for (int q = 0; q < 4; ++q) u[q] = __shfl(v[q], (lane + 32) & 63, WAVE);
-        if (c >= 2 || mt0 + j >= a.MT || m >= a.M) continue;
-        const int n0 = nt * 8 + c * 4;
-        float y[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + q < a.ntot ? n0 + q : a.ntot - 1;
-          const float bg = B0 ? bf16_to_f32(B0[n]) : 0.f, bu = B1 ? bf16_to_f32(B1[n]) : 0.f;
-          y[q] = silu(v[q] + bg) * (u[q] + bu);
-        }
-        if (a.Yp) {
+        for (int hb = 0; hb < 2; ++hb) {
+          const int nt = nt0 + 2 * i + hb;
+          if (nt >= a.NT) continue;
+          const int n0 = nt * 8 + 4 * lh;
           if (n0 >= a.ntot) continue;
+          float y[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) if (n0 + q >= a.ntot) y[q] = 0.f;
-          put_packed4(a.Yp, (size_t)a.MT * a.KTp * 512, a.KTp, m, n0, y);
-          continue;
-        }
-        float* py = a.Y + (size_t)m * a.ldy + n0;
-        if (n0 + 3 < a.ntot) *(float4*)py = make_float4(y[0], y[1], y[2], y[3]);
-        else for (int q = 0; q < 4; ++q) if (n0 + q < a.ntot) py[q] = y[q];
-      } else {
-        if (mt0 + j >= a.MT || m >= a.M) continue;
-        const int n0 = nt * 16 + c * 4;
-        float y[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + q < a.ntot ? n0 + q : a.ntot - 1;
-          float bv = 0.f;
-          if (B0) {
-            int seg = 0, loc = n;
-            if (loc >= a.N[0]) { loc -= a.N[0]; seg = 1; if (loc >= a.N[1]) { loc -= a.N[1]; seg = 2; } }
-            bv = bf16_to_f32((seg == 0 ? B0 : (seg == 1 ? B1 : B2))[loc]);
+          for (int q = 0; q < 4; ++q) {
+            const int n = n0 + q < a.ntot ? n0 + q : a.ntot - 1;
+            const float bg = B0 ? bf16_to_f32(B0[n]) : 0.f, bu = B1 ? bf16_to_f32(B1[n]) : 0.f;
+            y[q] = n0 + q < a.ntot ? silu(acc[i][j][8 * hb + q] + bg) * (acc[i][j][8 * hb + 4 + q] + bu) : 0.f;
           }
-          float t = v[q] + bv;
-          if (a.act == 1) t = gelu_erf(t);
-          else if (a.act == 2) t = fmaxf(t, 0.f);
-          if (a.Rsd) t += a.Rsd[(size_t)m * a.ldy + n];
-          y[q] = t;
+          if (a.Yp) { put_packed4(a.Yp, (size_t)a.MT * a.KTp * 512, a.KTp, m, n0, y); continue; }
+          float* py = a.Y + (size_t)m * a.ldy + n0;
+          if (n0 + 3 < a.ntot) *(float4*)py = make_float4(y[0], y[1], y[2], y[3]);
+          else for (int q = 0; q < 4; ++q) if (n0 + q < a.ntot) py[q] = y[q];
         }
-        if (a.Yp) {
-          if (n0 >= a.ntot) continue;
+      } else {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) if (n0 + q >= a.ntot) y[q] = 0.f;
-          put_packed4(a.Yp, (size_t)a.MT * a.KTp * 512, a.KTp, m, n0, y);
-          continue;
+        for (int gq4 = 0; gq4 < 4; ++gq4) {
+          const int n0 = (nt0 + 2 * i) * 16 + 8 * gq4 + 4 * lh;
+          if (n0 >= a.ntot) continue;
+          float y[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = n0 + q < a.ntot ? n0 + q : a.ntot - 1;
+            float bv = 0.f;
+            if (B0) {
+              int seg = 0, loc = n;
+              if (loc >= a.N[0]) { loc -= a.N[0]; seg = 1; if (loc >= a.N[1]) { loc -= a.N[1]; seg = 2; } }
+              bv = bf16_to_f32((seg == 0 ? B0 : (seg == 1 ? B1 : B2))[loc]);
+            }
+            float tv = acc[i][j][4 * gq4 + q] + bv;
+            if (a.act == 1) tv = gelu_erf(tv);
+            else if (a.act == 2) tv = fmaxf(tv, 0.f);
+            if (a.Rsd) tv += a.Rsd[(size_t)m * a.ldy + n];
+            y[q] = n0 + q < a.ntot ? tv : 0.f;
+          }
+          if (a.Yp) { put_packed4(a.Yp, (size_t)a.MT * a.KTp * 512, a.KTp, m, n0, y); continue; }
+          float* py = a.Y + (size_t)m * a.ldy + n0;
+          if (n0 + 3 < a.ntot) *(float4*)py = make_float4(y[0], y[1], y[2], y[3]);
+          else for (int q = 0; q < 4; ++q) if (n0 + q < a.ntot) py[q] = y[q];
         }
-        float* py = a.Y + (size_t)m * a.ldy + n0;
-        if (n0 + 3 < a.ntot) *(float4*)py = make_float4(y[0], y[1], y[2], y[3]);
-        else for (int q = 0; q < 4; ++q) if (n0 + q < a.ntot) py[q] = y[q];
       }
     }
   }
@@ -321,7 +383,8 @@ struct PKvPackArgs {
   const float* qkv;     // [M][3 * d_model]: q | k | v as the projection left them
   const float2* rope;   // [max_ctx][hd / 2] or null
   uint16_t* Qp; uint16_t* Kp; uint16_t* Vp;
-  int M, H, d_model, JP;
+  float* Kc; float* Vc; // this layer's fp32 cache (the decode path's blocks): positions 0 .. M - 1 are filled as well
+  int M, H, d_model, JP, max_ctx;
   float scale;          // factor on the queries: log2(e) / sqrt(hd), the softmax being evaluated as 2^(s - max)
 };
 struct PAttnArgs {
@@ -369,6 +432,10 @@ __global__ __launch_bounds__(256) void pkv_pack_kernel(PKvPackArgs a) {
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) q[u] *= a.scale;         // (scale carries log2(e): the attention kernel works with powers of two)
+      // the cache takes the key as the decode path stores it: four components of one position are adjacent
+      float* const kc = a.Kc + (size_t)h * kv_blocks(a.max_ctx) * (KV_BLOCK * HD);
+      *(float4*)(kc + k_index(m, i0, HD)) = make_float4(k[0], k[1], k[2], k[3]);
+      *(float4*)(kc + k_index(m, i0 + 4, HD)) = make_float4(k[4], k[5], k[6], k[7]);
     }
     const size_t o = ((((size_t)h * 2 * a.JP + 2 * jp + (rl >> 4)) * CB + (c8 >> 2)) * 64 + (rl & 15) + 16 * (c8 & 3)) * 8;
     uint4 hi, lo;
@@ -390,6 +457,15 @@ __global__ __launch_bounds__(256) void pkv_pack_kernel(PKvPackArgs a) {
     uint4 hi, lo;
     split2(v, hi, lo);
     *(uint4*)(a.Vp + o) = hi; *(uint4*)(a.Vp + plane + o) = lo;
+    // the cache holds four consecutive positions of one component side by side: the lane's two quadruples
+    float* const vc = a.Vc + (size_t)h * kv_blocks(a.max_ctx) * (KV_BLOCK * HD);
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      const int m0 = 32 * jp + 16 * x + 4 * c;
+      float* const dst = vc + v_index(m0, 16 * ct + i, HD);
+      if (m0 + 3 < a.M) *(float4*)dst = make_float4(v[4 * x], v[4 * x + 1], v[4 * x + 2], v[4 * x + 3]);
+      else for (int u = 0; u < 4; ++u) if (m0 + u < a.M) dst[u] = v[4 * x + u];
+    }
   }
 }
 

@@ -2,9 +2,6 @@
 #define PPD_PREFILL_TU 1
 #include "ppd_prefill.h"
 
-#ifndef PPD_PATTN_QT
-#define PPD_PATTN_QT 0   // 1, 2, 4: force the query tiles per wave (measurement builds)
-#endif
 
 namespace ppd {
 
@@ -14,26 +11,26 @@ hipError_t launch_pack_rows(hipStream_t stream, const PackArgs& a) {
   return hipGetLastError();
 }
 
-hipError_t launch_pgemm(hipStream_t stream, PGemmArgs a, bool paired) {
-  if (a.M < 1 || a.MT != (a.M + 15) / 16 || a.KT < 1 || a.NT < 1) return hipErrorInvalidValue;
-  // narrow matrices take two tiles per wave so that the grid still fills the machine
-  const int mb = (a.MT + PG_TM - 1) / PG_TM;
-  const int tn = ((a.NT + PG_WAVES * 4 - 1) / (PG_WAVES * 4)) * mb >= 384 ? 4 : 2;
-  a.MB = mb;
-  a.NB = (a.NT + PG_WAVES * tn - 1) / (PG_WAVES * tn);
-  a.GM = mb < PG_GROUP_M ? mb : PG_GROUP_M;
+template <bool PAIRED, int TN, int TMB>
+static hipError_t launch_pgemm_t(hipStream_t stream, PGemmArgs a) {
+  a.MB = (a.MT + TMB - 1) / TMB;
+  a.NB = (a.NT + PG_WAVES * TN - 1) / (PG_WAVES * TN);
+  a.GM = a.MB < PG_GROUP_M ? a.MB : PG_GROUP_M;
   a.GQ = PG_GROUP_Q;
-  a.MBG = (mb + a.GM - 1) / a.GM;
+  a.MBG = (a.MB + a.GM - 1) / a.GM;
   const int nbq = (a.NB + 7) / 8;
   const dim3 grid(8 * ((nbq + a.GQ - 1) / a.GQ) * a.GQ * a.MBG * a.GM);
-  if (paired) {
-    if (tn == 4) hipLaunchKernelGGL((pgemm_kernel<true, 4>), grid, dim3(PG_THREADS), 0, stream, a);
-    else hipLaunchKernelGGL((pgemm_kernel<true, 2>), grid, dim3(PG_THREADS), 0, stream, a);
-  } else {
-    if (tn == 4) hipLaunchKernelGGL((pgemm_kernel<false, 4>), grid, dim3(PG_THREADS), 0, stream, a);
-    else hipLaunchKernelGGL((pgemm_kernel<false, 2>), grid, dim3(PG_THREADS), 0, stream, a);
-  }
+  hipLaunchKernelGGL((pgemm_kernel<PAIRED, TN, TMB>), grid, dim3(PG_THREADS), (size_t)PG_R * PG_STAGE_BLKS * 1024, stream, a);
   return hipGetLastError();
+}
+
+hipError_t launch_pgemm(hipStream_t stream, PGemmArgs a, bool paired) {
+  if (a.M < 1 || a.MT != (a.M + 15) / 16 || a.KT < 1 || a.NT < 1) return hipErrorInvalidValue;
+  // narrow matrices take two blocks per wave so that the grid still fills the machine
+  const int mb = (a.MT + 3) / 4;
+  const int tn = ((a.NT + PG_WAVES * 4 - 1) / (PG_WAVES * 4)) * mb >= 384 ? 4 : 2;
+  if (paired) return tn == 4 ? launch_pgemm_t<true, 4, 4>(stream, a) : launch_pgemm_t<true, 2, 4>(stream, a);
+  return tn == 4 ? launch_pgemm_t<false, 4, 4>(stream, a) : launch_pgemm_t<false, 2, 4>(stream, a);
 }
 
 hipError_t launch_pkv_pack(hipStream_t stream, const PKvPackArgs& a, int head_dim) {
@@ -55,10 +52,11 @@ static hipError_t launch_pattn_t(hipStream_t stream, const PAttnArgs& a) {
 
 hipError_t launch_pattn(hipStream_t stream, const PAttnArgs& a, int head_dim) {
   if (a.M < 1 || a.JP != (a.M + 31) / 32 || (head_dim != 64 && head_dim != 128) || a.d_model % 32) return hipErrorInvalidValue;
-  // rows per workgroup (64 QT): more for long prompts, whose workgroups are plenty
-  const int qt = PPD_PATTN_QT ? PPD_PATTN_QT : (a.M >= 2048 ? 4 : (a.M >= 1024 ? 2 : 1));
-  if (head_dim == 128) return qt == 4 ? launch_pattn_t<128, 4>(stream, a) : (qt == 2 ? launch_pattn_t<128, 2>(stream, a) : launch_pattn_t<128, 1>(stream, a));
-  return qt == 4 ? launch_pattn_t<64, 4>(stream, a) : (qt == 2 ? launch_pattn_t<64, 2>(stream, a) : launch_pattn_t<64, 1>(stream, a));
+  // rows per workgroup (64 QT): two query tiles per wave once the prompt gives enough workgroups (four would leave
+  // one wave per SIMD: measured slower)
+  const bool two = a.M >= 1024;
+  if (head_dim == 128) return two ? launch_pattn_t<128, 2>(stream, a) : launch_pattn_t<128, 1>(stream, a);
+  return two ? launch_pattn_t<64, 2>(stream, a) : launch_pattn_t<64, 1>(stream, a);
 }
 
 }  // namespace ppd
