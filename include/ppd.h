@@ -130,12 +130,19 @@ int ppd_reset(ppd_ctx *ctx);
  * run through all d layers to fill the KV cache, the last prompt token
  * becomes x_0 with match = False.  Implies ppd_reset.  PPD_ECTX if
  * n_prompt > max_ctx; PPD_EINVAL for ids outside [0, vocab).
- * The prompt goes through the decode kernels in chunks of consecutive
- * positions (16 for bf16 weights, 8 for fp32; PPD_PREFILL_CHUNK lowers it):
- * one pass over the weights per chunk, rows of a chunk attending
- * causally to each other.  Every row's arithmetic is that of a one-token
- * pass, so the cache equals a token-by-token prefill bit for bit
- * (PPD_PREFILL_CHUNK=1 in the environment at ppd_create runs that). */
+ * bf16 models with prompts of more than 32 tokens: all prompt rows go through
+ * a layer at once (tiled MFMA GEMMs on rows split into two bf16 terms,
+ * causal attention on the same operands): products exact in fp32 as in
+ * decoding, other summation order, so the cache is close to, not
+ * bit-identical with, a token-by-token pass (every decode step after it is
+ * the same arithmetic either way).  Otherwise, or with PPD_PREFILL_TILED=2 /
+ * PPD_PREFILL_CHUNK=n in the environment at ppd_create, the prompt goes
+ * through the decode kernels in chunks of consecutive positions (16 for
+ * bf16 weights, 8 for fp32; n lowers it): one pass over the weights per
+ * chunk, every row's arithmetic that of a one-token pass, the cache equal to
+ * a token-by-token prefill bit for bit (n = 1 runs exactly that).
+ * Buffers of the first kind are allocated at the first such prompt and grow
+ * with the longest prompt seen (PPD_ENOMEM / PPD_EHIP if that fails). */
 int ppd_prefill(ppd_ctx *ctx, const int32_t *prompt, int n_prompt);
 
 /* One round of Algorithm 2: main token to the exit layer (from layer 1, or

@@ -68,7 +68,7 @@ struct ppd_ctx {
   int last_kind;         // kind of the last round (which buffer holds its early logits)
   int prefill_chunk;     // prompt positions per chunk
   // compute-bound prompt pass (bf16 models, prompts of at least PREFILL_TILED_MIN rows): all rows at once through
-  // tiled MFMA GEMMs and causal attention over the cache; its buffers are made at the first such prompt
+  // tiled MFMA GEMMs and causal attention over two-term operand blocks; its buffers are made at the first such prompt
   int prefill_tiled;
   int pf_rows;           // rows the buffers below hold
   float *pf_h, *pf_qkv;  // [pf_rows][d_model | 3 d_model]
