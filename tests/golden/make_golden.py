@@ -7,7 +7,10 @@ generated position, its final-layer and early-exit logits at a fixed sample of v
 plus its top-8 (ids and values).  The early-exit logits and the tokens do not depend on k, so the
 oracle's PPD loop is run with k = 1 (Algorithm 2; exit layer of the configuration).
 
-Usage: python tests/golden/make_golden.py llama7b [llama7b_a0p1 ...]
+With --full, writes tests/golden/<config>_full.npz instead: every logit of the vocabulary (final and early) at the
+first, the middle and the last generated position, from the same oracle run.
+
+Usage: python tests/golden/make_golden.py [--full] llama7b [llama7b_a0p1 ...]
 """
 import os
 import sys
@@ -34,7 +37,7 @@ def top(z):
     return order.astype(np.int32), z[order]
 
 
-def make(name, n_gen=None):
+def make(name, n_gen=None, full=False):
     cfg = pi.CONFIGS[name]
     ell = n_gen or cfg.n_gen
     t0 = time.time()
@@ -43,6 +46,16 @@ def make(name, n_gen=None):
     o = oracle.Oracle(m, ctx_cap=cfg.n_prompt + ell + 1)
     print(name, "weights ready", round(time.time() - t0, 1), "s", flush=True)
     r = o.ppd(prompt, ell, 1, cfg.exit_layer, want_logits=True)
+    if full:
+        pos = np.array(sorted({0, ell // 2, ell - 1}), dtype=np.int32)
+        np.savez_compressed(
+            os.path.join(HERE, name + "_full.npz"),
+            config=name, n_prompt=cfg.n_prompt, n_gen=ell, exit_layer=cfg.exit_layer,
+            weights_checksum=np.uint64(m.checksum()), tokens=r["tokens"], positions=pos,
+            final_logits=r["final_logits"][pos].astype(np.float32),
+            early_logits=r["early_logits"][pos].astype(np.float32))
+        print(name, "full logits done in", round(time.time() - t0, 1), "s", flush=True)
+        return
     ids = sample_ids(cfg)
     ft = [top(z) for z in r["final_logits"]]
     et = [top(z) for z in r["early_logits"]]
@@ -58,6 +71,8 @@ def make(name, n_gen=None):
 
 
 if __name__ == "__main__":
-    for arg in sys.argv[1:]:
+    args = sys.argv[1:]
+    full = "--full" in args
+    for arg in (a for a in args if a != "--full"):
         n, _, g = arg.partition(":")
-        make(n, int(g) if g else None)
+        make(n, int(g) if g else None, full)

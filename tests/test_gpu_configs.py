@@ -73,6 +73,13 @@ def check_against_golden(name, gname, ks):
     otoks, ids = g["tokens"], g["sample_ids"]
     ell, tol = len(otoks), 2e-2
     e = cfg.exit_layer
+    # every logit of the vocabulary at a few positions, where such a file was stored
+    full, fpath = {}, os.path.join(GOLD, gname + "_full.npz")
+    if os.path.exists(fpath):
+        gf = np.load(fpath)
+        if int(gf["weights_checksum"]) == m.checksum() and np.array_equal(gf["tokens"], otoks):
+            full = {int(p): (gf["final_logits"][i], gf["early_logits"][i]) for i, p in enumerate(gf["positions"])}
+    worst_full = 0.0
     # plain greedy along the oracle's sequence: sampled logits, top-8, tokens
     P = binding.PPD(cfg, dev, k=ks[0])
     P.ppd_prefill(prompt)
@@ -86,6 +93,8 @@ def check_against_golden(name, gname, ks):
         err = max(np.abs(z[ids] - g["final_samples"][t]).max(), np.abs(z[g["final_top_ids"][t]] - g["final_top_vals"][t]).max())
         worst = max(worst, float(err))
         assert err <= tol, f"{name}: final logits off by {err} at step {t}"
+        if t in full and resyncs == 0:
+            worst_full = max(worst_full, float(np.abs(z - full[t][0]).max()))
         if tok != int(otoks[t]):
             top_ids, top_vals = list(g["final_top_ids"][t]), g["final_top_vals"][t]
             assert tok in top_ids and top_vals[0] - top_vals[top_ids.index(tok)] < tol, f"{name}: token differs beyond margin at step {t}"
@@ -93,6 +102,9 @@ def check_against_golden(name, gname, ks):
             P.ppd_prefill(list(prompt) + [int(x) for x in otoks[:t + 1]])
     print(name, "plain vs stored oracle: max|dlogit|", worst, "resyncs", resyncs, flush=True)
     assert worst <= tripwire(cfg), f"{name}: {worst:.3g} is within the tolerance but past the regression tripwire"
+    if full:
+        print(name, "all", cfg.vocab, "logits at positions", sorted(full), ": max|dlogit|", worst_full, flush=True)
+        assert worst_full <= tripwire(cfg)
     for k in ks:
         Pk = binding.PPD(cfg, dev, k=k) if k != ks[0] else P
         Pk.ppd_prefill(prompt)
@@ -102,6 +114,8 @@ def check_against_golden(name, gname, ks):
             ze = Pk.ppd_get_early_logits()
             err = max(np.abs(ze[ids] - g["early_samples"][t]).max(), np.abs(ze[g["early_top_ids"][t]] - g["early_top_vals"][t]).max())
             assert err <= tol, f"{name} k={k}: early logits off by {err} at step {t}"
+            if t in full and not resynced:
+                assert np.abs(ze - full[t][1]).max() <= tripwire(cfg), f"{name} k={k}: an early logit outside the stored sample is off at step {t}"
             cand = list(info.cand)[:k]
             kth = g["early_top_vals"][t][k - 1]
             for c in cand:      # every candidate is within tol of making the oracle's top-k
