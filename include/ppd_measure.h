@@ -53,7 +53,8 @@ int ppd_get_kernel_time(ppd_ctx *ctx, int kernel_class, int groups, double *ms_t
 int ppd_time_ffn_in(ppd_ctx *ctx, int reps, int groups, double *ms_per_launch);
 
 /* Measurement aid (not part of the method): read `bytes` of DEVICE memory at dev_buf `iters` times with a
- * kernel that does nothing but non-temporal 16-byte loads (a few launch shapes, the best counts), and report the rate in GB/s (HOST
+ * kernel that does nothing but non-temporal 16-byte loads (a few launch shapes and two walks -- grid-stride, and one
+ * contiguous part per workgroup --, the best counts), and report the rate in GB/s (HOST
  * output): the streaming rate this GPU reaches, next to which the decode kernels' rates are read.
  * bytes must be a positive multiple of 16; the buffer is only read.  Runs on its own stream, synchronous. */
 int ppd_stream_read_probe(const void *dev_buf, uint64_t bytes, int iters, double *gbps);
