@@ -19,6 +19,11 @@ SMALL = {
     "llama_long": small_cfg("llama", max_ctx=420, n_prompt=300, n_gen=24),
     "opt_long": small_cfg("opt", max_ctx=300, n_prompt=250, n_gen=16),
 }
+# prompts past 1024 rows: the prompt attention's two-tiles-per-wave instances, ragged last tiles
+XLONG = {
+    "llama_xlong": small_cfg("llama", max_ctx=1160, n_prompt=1102, n_gen=6),
+    "opt_xlong": small_cfg("opt", max_ctx=1100, n_prompt=1038, n_gen=6),
+}
 
 
 @pytest.fixture(scope="module", params=list(SMALL))
@@ -351,6 +356,32 @@ def test_separate_early_head_matches_oracle_and_keeps_the_output(family, near):
         assert np.abs(Pd.ppd_get_early_logits() - P.ppd_get_early_logits()).max() > 1e-2
         Pd.close()
         P.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", ["llama_xlong", "opt_xlong"])
+def test_compute_bound_prompt_pass_beyond_1024_rows(name, monkeypatch):
+    """Prompts of 1024 rows and more take the attention instance with two query tiles per wave (head dimensions 128
+    and 64 here), with a ragged last tile, a ragged last 32-row step and a last workgroup that is partly empty.
+    Checked as for shorter prompts: next-token logits against the oracle, and against the row-chunk path."""
+    cfg = XLONG[name]
+    m = pi.make_model(cfg)
+    dev = binding.upload_model(m)
+    o = oracle.Oracle(m)
+    for n_prompt in (1025, cfg.n_prompt):
+        prompt = pi.make_prompt(cfg, n_prompt)
+        ro = o.ppd(prompt, 4, 3, cfg.exit_layer, want_logits=True)
+        monkeypatch.setenv("PPD_PREFILL_TILED", "1")
+        P = binding.PPD(cfg, dev, k=3)
+        r = run_against_oracle(P, prompt, "ppd", ro["tokens"], ro["final_logits"], ro["early_logits"], tol=TOL[cfg.wdtype])
+        toks, z, _ = gpu_generate(P, prompt, 4, "ppd")
+        P.close()
+        monkeypatch.setenv("PPD_PREFILL_TILED", "2")
+        Q = binding.PPD(cfg, dev, k=3)
+        qtoks, qz, _ = gpu_generate(Q, prompt, 4, "ppd")
+        Q.close()
+        print(name, n_prompt, "worst |dlogit| vs oracle", r["max_err"], "vs row chunks", float(np.abs(z - qz).max()), flush=True)
+        assert np.abs(z - qz).max() <= 1e-4
 
 
 @pytest.mark.gpu
