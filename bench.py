@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # (paper_2307_05908_amd/ppd_pmc_probe), see profiles/.  A property of the kernel source it was collected on.
 MEASURED_TRAFFIC = {("llama7b", 3): 361.75e6}
 # sha1 of csrc/ppd_kernels.h when the counters were collected: a changed kernel source voids the figure (null is printed)
-TRAFFIC_KERNELS_SHA1 = "f5a89d12e3b9190c815472e09b4e06c36a5c6789"
+TRAFFIC_KERNELS_SHA1 = "009930545f1fa5ba9fbe0077f60eaffaf9e4f03d"
 TRAFFIC_SOURCE = "profiles/llama7b_ppd_k3_traffic.txt"
 
 

@@ -451,6 +451,7 @@ EmbedArgs embed_args(ppd_ctx* c, const int32_t* ids_dev, int rows, int row0, int
   EmbedArgs a;
   a.tok_emb = c->tok_emb; a.pos_emb = c->d.pos == 0 ? c->pos_emb : nullptr; a.ids = ids_dev; a.ds = c->ds;
   a.h = c->h + (size_t)row0 * c->d.d_model; a.rows = rows; a.d_model = c->d.d_model; a.pos_off = pos_off; a.pos_step = 0;
+  a.vocab = c->d.vocab;
   return a;
 }
 
@@ -514,6 +515,7 @@ int run_head(ppd_ctx* c, bool early, bool adopt) {
   s.pk_val = c->pk_val; s.pk_idx = c->pk_idx; s.nblk = c->head_grid; s.kk = topk;
   s.pk_stride = (int)c->pk_slots;
   s.k = adopt || early ? c->k : 0; s.mode = early ? 0 : 1; s.ds = c->ds; s.host_result = c->host_result_dev;
+  s.vocab = d.vocab;
   dim3 grid(1, 1);
   if (early) {
     s.emb = embed_args(c, nullptr, c->k, 1, 1);

@@ -168,10 +168,14 @@ struct EmbedArgs {
   float* h;             // [rows][d_model]
   int rows, d_model, pos_off;   // the rows sit at position ds->pos + pos_off (+ r * pos_step for row r)
   int pos_step;
+  int vocab;            // rows of tok_emb
 };
+// An id outside the vocabulary can only come out of a selection over logits that are not numbers (every comparison
+// with a NaN fails, and the "nothing found" id stays): it must never become an address.
+__device__ __forceinline__ int id_in_vocab(int id, int vocab) { return (unsigned)id < (unsigned)vocab ? id : 0; }
 template <typename WT>
 __device__ __forceinline__ void embed_rows(const EmbedArgs& a, int r, int i0, int stride) {
-  int tok = a.ids[r];
+  const int tok = id_in_vocab(a.ids[r], a.vocab);
   int pos = a.ds->pos + a.pos_off + r * a.pos_step;
   for (int i = i0; i < a.d_model; i += stride) {
     float v = WTr<WT>::load1(a.tok_emb, (size_t)tok * a.d_model + i);
@@ -1281,7 +1285,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
     if (blockIdx.x == 0 && blockIdx.y == 0 && tid < a.k) { a.ds->cand[tid] = win[tid]; a.host_result[2 + tid] = win[tid]; }
     const int r = blockIdx.y;
     EmbedArgs e = a.emb;
-    int tok = win[r];
+    const int tok = id_in_vocab(win[r], a.vocab);
     int pos = a.ds->pos + e.pos_off;
     for (int i = blockIdx.x * SEL_THREADS + tid; i < e.d_model; i += gridDim.x * SEL_THREADS) {
       float v = WTr<WT>::load1(e.tok_emb, (size_t)tok * e.d_model + i);
@@ -1304,7 +1308,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
     }
     __syncthreads();
   }
-  const int token = a.samp_topk > 0 ? s_tok : (a.sampled ? a.ds->sampled : win[0]);
+  const int token = id_in_vocab(a.samp_topk > 0 ? s_tok : (a.sampled ? a.ds->sampled : win[0]), a.vocab);
   if (tid == 0) {
     int midx = -1;
     for (int q = 0; q < a.k; ++q) if (a.ds->cand[q] == token) { midx = q; break; }
@@ -1348,7 +1352,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
       a.h[i] = a.h[(size_t)(1 + midx) * a.d_model + i];
       if (pos2 < a.max_ctx)
         for (int r = 0; r < a.k; ++r) {
-          float v = WTr<WT>::load1(e.tok_emb, (size_t)win[r] * e.d_model + i);
+          float v = WTr<WT>::load1(e.tok_emb, (size_t)id_in_vocab(win[r], a.vocab) * e.d_model + i);
           if (e.pos_emb) v += WTr<WT>::load1(e.pos_emb, (size_t)pos2 * e.d_model + i);
           e.h[(size_t)r * e.d_model + i] = v;
         }
