@@ -118,7 +118,10 @@ typedef struct {
  * again at every step and must not change.  Every call is synchronous: the
  * context's stream is idle on return.  The KV cache, the candidates' KV
  * tails and all scratch are allocated here (device memory, freed by
- * ppd_destroy).  *out receives the context (HOST). */
+ * ppd_destroy).  *out receives the context (HOST).  PPD_ELIMIT for a model
+ * one of whose matrices, as launched (Q|K|V together, gate|up together, the
+ * LM head), reaches 4 GiB (rows padded to 16, columns to 32): the kernels
+ * address a matrix with 32-bit byte offsets. */
 int ppd_create(const ppd_model_dims *dims, const ppd_weights *w, int k, int exit_layer,
                void *hip_stream, ppd_ctx **out);
 

@@ -772,6 +772,14 @@ int ppd_create(const ppd_model_dims* dims, const ppd_weights* w, int k, int exit
     return PPD_EINVAL;
   if (k < 1 || k > PPD_MAX_K || k > d.vocab) return PPD_EINVAL;
   if (2 * exit_layer < d.n_layers || exit_layer > d.n_layers - 1) return PPD_EINVAL;   // Theorem 4.1: dbar >= d/2
+  {
+    // the kernels address one weight matrix (as launched: Q|K|V together, gate|up together) with 32-bit byte offsets
+    const int64_t esz = d.wdtype == 0 ? 4 : 2;
+    auto padded = [esz](int64_t rows, int64_t cols) { return ((rows + 15) / 16 * 16) * ((cols + 31) / 32 * 32) * esz; };
+    const int64_t lim = (int64_t)1 << 32, dm = d.d_model, F = d.d_ff;
+    if (padded(3 * dm, dm) >= lim || padded((d.act == 2 ? 2 : 1) * F, dm) >= lim || padded(dm, F) >= lim || padded(d.vocab, dm) >= lim)
+      return PPD_ELIMIT;
+  }
   if (!w->tok_emb || !w->lm_head || !w->lnf_g || (d.pos == 0 && !w->pos_emb) || (d.norm == 0 && !w->lnf_b))
     return PPD_EINVAL;
   if (!w->ln1_g || !w->wq || !w->wk || !w->wv || !w->wo || !w->ln2_g || !w->w_in || !w->w_out) return PPD_EINVAL;

@@ -57,6 +57,19 @@ def test_create_rejects_bad_arguments(kw, k, e):
     assert not h.value
 
 
+def test_create_rejects_a_matrix_beyond_32_bit_offsets():
+    """The kernels address one weight matrix with 32-bit byte offsets: a model whose LM head (or fused projection)
+    reaches 4 GiB is refused with PPD_ELIMIT before anything is allocated or read."""
+    lib = binding.load_library()
+    h = ctypes.c_void_p()
+    w = binding.Weights()
+    big_head = _dims(d_model=8192, n_heads=64, head_dim=128, d_ff=8192, vocab=200000)      # 200000 x 8192 x 4 B = 6.5 GB
+    assert lib.ppd_create(ctypes.byref(big_head), ctypes.byref(w), 3, 2, None, ctypes.byref(h)) == -6
+    big_ffn = _dims(d_model=16384, n_heads=128, head_dim=128, d_ff=65536, act=2, vocab=1024)   # gate|up: 2 x 65536 x 16384 x 4 B
+    assert lib.ppd_create(ctypes.byref(big_ffn), ctypes.byref(w), 3, 2, None, ctypes.byref(h)) == -6
+    assert not h.value
+
+
 def test_null_arguments():
     lib = binding.load_library()
     assert lib.ppd_create(None, None, 3, 2, None, None) == -1
